@@ -1,0 +1,124 @@
+"""Plain fp64 CPU oracle for one scaled-Muon optimizer step on one 2-D matrix.
+
+TEST INFRASTRUCTURE ONLY: this module exists to check the HIP library and to be
+timed as the CPU baseline.  The product package never imports it, and it shares
+no code, tables or helpers with the HIP path.
+
+The method is an iteration (a fixed number of Newton-Schulz steps, not the exact
+polar factor), so the oracle is the algorithm itself, step by step, in the
+paper's order and notation, in IEEE double precision.  numpy's ``@`` (a library
+matmul) is the only primitive used; there is no blocking, fusion or reordering.
+
+Every function is pinned by tests that do not call it to produce the expected
+value (SVD closed form, exact rational scalar orbits, hand-worked 2x2 cases,
+pure-Python brute force, symmetries, the singular-value band, Lemma 1).
+Nothing here is "parity unpinned".
+
+Notation (paper section 2.1 and 2.2): W weight [A, B]; G gradient; M momentum;
+mu momentum coefficient; eta learning rate; lambda weight-decay ratio; N number
+of Newton-Schulz iterations; (a, b, c) the quintic's coefficients; O the
+orthogonalised update.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# Coefficients and defaults stated in section 2.1 (coefficients) and
+# section 2.2 "Other Hyper-parameters" / "Matching update RMS of AdamW".
+NS_A, NS_B, NS_C = 3.4445, -4.7750, 2.0315
+DEFAULT_MU = 0.95
+DEFAULT_NS_STEPS = 5
+DEFAULT_RMS_SCALE = 0.2
+
+
+def _f64(x) -> np.ndarray:
+    """Widen an array exactly to float64 (every fp32/bf16 value is a double)."""
+    return np.asarray(x, dtype=np.float64)
+
+
+def momentum_update(M_prev, G, mu: float) -> np.ndarray:
+    """M_t = mu * M_{t-1} + grad   (first line of the update rule, section 2.1)."""
+    return float(mu) * _f64(M_prev) + _f64(G)
+
+
+def ns_input(M_t, G, mu: float, nesterov: bool) -> np.ndarray:
+    """Matrix handed to Newton-Schulz.
+
+    Plain momentum feeds M_t (Eq. 1).  The Nesterov-style variant the paper says
+    it uses in practice (footnote 1 of section 2.1) feeds mu * M_t + grad.
+    """
+    if nesterov:
+        return float(mu) * _f64(M_t) + _f64(G)
+    return _f64(M_t).copy()
+
+
+def frobenius_normalize(U, eps: float = 0.0) -> np.ndarray:
+    """X_0 = U / ||U||_F  (section 2.1, "Newton-Schulz Iterations ...").
+
+    The paper has no epsilon; ``eps`` is added to the norm so that an all-zero
+    input gives X_0 = 0 instead of 0/0.  With eps = 0 this is the paper's formula.
+    """
+    U = _f64(U)
+    norm = np.sqrt(np.sum(U * U))
+    return U / (norm + float(eps))
+
+
+def newton_schulz_iterate(X0, steps: int = DEFAULT_NS_STEPS,
+                          a: float = NS_A, b: float = NS_B, c: float = NS_C) -> np.ndarray:
+    """N applications of Eq. 2:  X_k = a X + b (X X^T) X + c (X X^T)^2 X.
+
+    Written exactly as printed: the Gram matrix X X^T, its square, and the three
+    terms summed.  Works for any shape (the formula never transposes).
+    """
+    X = _f64(X0).copy()
+    for _ in range(int(steps)):
+        XXt = X @ X.T
+        X = a * X + b * (XXt @ X) + c * ((XXt @ XXt) @ X)
+    return X
+
+
+def newton_schulz(U, steps: int = DEFAULT_NS_STEPS, a: float = NS_A, b: float = NS_B,
+                  c: float = NS_C, eps: float = 0.0, orient: bool = True) -> np.ndarray:
+    """O = Newton-Schulz(U): normalise, orient so rows <= cols, iterate, orient back.
+
+    The paper never transposes; because the quintic is odd, iterating on U^T and
+    transposing the result is the same map in exact arithmetic (only the size of
+    the Gram matrix changes).  ``orient=False`` runs the formula as printed.
+    """
+    U = _f64(U)
+    X0 = frobenius_normalize(U, eps)
+    transposed = orient and U.shape[0] > U.shape[1]
+    if transposed:
+        X0 = X0.T
+    X = newton_schulz_iterate(X0, steps, a, b, c)
+    return X.T.copy() if transposed else X
+
+
+def apply_update(W_prev, O, lr: float, weight_decay: float,
+                 rms_scale: float = DEFAULT_RMS_SCALE) -> np.ndarray:
+    """W_t = W_{t-1} - eta * (rms_scale * sqrt(max(A, B)) * O + lambda * W_{t-1}).
+
+    Eq. 4 (which contains the decoupled weight decay of Eq. 3); rms_scale is the
+    paper's 0.2; [A, B] is the shape of the matrix as passed.
+    """
+    W_prev = _f64(W_prev)
+    A, B = W_prev.shape
+    scale = float(rms_scale) * np.sqrt(float(max(A, B)))
+    return W_prev - float(lr) * (scale * _f64(O) + float(weight_decay) * W_prev)
+
+
+def update_rms(O) -> float:
+    """sqrt(mean(u^2)) of the orthogonalised update (return value of Algorithm 1)."""
+    O = _f64(O)
+    return float(np.sqrt(np.mean(O * O)))
+
+
+def muon_step(W_prev, G, M_prev, *, lr: float, weight_decay: float, mu: float = DEFAULT_MU,
+              ns_steps: int = DEFAULT_NS_STEPS, a: float = NS_A, b: float = NS_B, c: float = NS_C,
+              rms_scale: float = DEFAULT_RMS_SCALE, eps: float = 0.0, nesterov: bool = True):
+    """One whole step on one matrix.  Returns (W_t, M_t, O_t) in float64."""
+    M = momentum_update(M_prev, G, mu)
+    U = ns_input(M, G, mu, nesterov)
+    O = newton_schulz(U, ns_steps, a, b, c, eps)
+    W = apply_update(W_prev, O, lr, weight_decay, rms_scale)
+    return W, M, O
