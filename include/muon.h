@@ -1,0 +1,135 @@
+/*
+ * muon.h - C ABI of the MI355X (gfx950) scaled-Muon optimizer step.
+ *
+ * One call to muon_step() performs, for every 2-D matrix in a list, the update
+ * rule of "Muon is Scalable for LLM Training" (arXiv 2502.16982):
+ *
+ *   M_t = mu * M_{t-1} + G                                  (section 2.1, update rule, line 1)
+ *   U   = M_t            or   mu * M_t + G  (Nesterov)      (section 2.1, footnote 1)
+ *   X_0 = U / (||U||_F + eps), transposed so rows <= cols   (section 2.1, "Newton-Schulz Iterations")
+ *   X_k = a X + b (X X^T) X + c (X X^T)^2 X,  k = 1..N      (Eq. 2)
+ *   O   = X_N (transposed back)                             (Eq. 1)
+ *   W_t = W_{t-1} - lr * (rms_scale * sqrt(max(A,B)) * O + weight_decay * W_{t-1})   (Eq. 4, contains Eq. 3)
+ *
+ * All buffer pointers are DEVICE pointers owned by the caller.  The library
+ * never allocates device memory: it works inside a caller-provided workspace.
+ * Every function returns MUON_OK (0) or a negative muon_status; nothing here
+ * throws, aborts or prints.  A context is not thread-safe; distinct contexts are
+ * independent.  All work of muon_step() is enqueued on the caller's HIP stream
+ * and the call returns without synchronising with the device.
+ */
+#ifndef MUON_H_
+#define MUON_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MUON_F32 = 0,   /* IEEE binary32 */
+  MUON_BF16 = 1   /* bfloat16 (upper 16 bits of a binary32, round-to-nearest-even on store) */
+} muon_dtype;
+
+typedef enum {
+  MUON_OK = 0,
+  MUON_E_INVALID_ARG = -1,         /* null pointer, n <= 0, rows/cols < 1, bad hyper-parameter        */
+  MUON_E_UNSUPPORTED_DTYPE = -2,   /* a dtype field is neither MUON_F32 nor MUON_BF16                  */
+  MUON_E_SHAPE_MISMATCH = -3,      /* the list given to muon_step differs from the one given to init   */
+  MUON_E_WORKSPACE_TOO_SMALL = -4, /* workspace cannot hold the tables plus the largest single matrix  */
+  MUON_E_HIP = -5,                 /* a HIP runtime call failed (see muon_last_hip_error)              */
+  MUON_E_NOT_RESIDENT = -6,        /* debug read of a matrix whose workspace has been reused           */
+  MUON_E_MISALIGNED = -7           /* a buffer pointer is not aligned to its element size              */
+} muon_status;
+
+/* One 2-D parameter.  W, G and M are rows x cols, row-major, contiguous. */
+typedef struct {
+  void* w;              /* device; weight W_{t-1}, dtype w_dtype; overwritten with W_t                 */
+  const void* g;        /* device; gradient of this step, dtype g_dtype; read only                     */
+  float* m;             /* device; fp32 momentum M_{t-1}; overwritten with M_t; zero before step 1     */
+  int64_t rows, cols;   /* A, B of section 2.2 (the matrix as the model defines it, un-sharded)        */
+  int32_t w_dtype;      /* muon_dtype                                                                  */
+  int32_t g_dtype;      /* muon_dtype                                                                  */
+} muon_param;
+
+/* Hyper-parameters of one step (all may change from step to step). */
+typedef struct {
+  double lr;            /* eta_t                                             */
+  double weight_decay;  /* lambda of Eq. 3                                   */
+  double momentum;      /* mu                                                */
+  double a, b, c;       /* quintic coefficients of Eq. 2 (3.4445, -4.7750, 2.0315) */
+  double rms_scale;     /* the 0.2 of Eq. 4                                  */
+  double eps;           /* added to ||U||_F; 0 reproduces the paper's formula, >0 guards an all-zero U */
+  int32_t ns_steps;     /* N >= 0 (the paper uses 5)                         */
+  int32_t nesterov;     /* 0: U = M_t;  1: U = mu*M_t + G                    */
+} muon_hparams;
+
+typedef struct muon_ctx muon_ctx;
+
+/* Fills *hp with the paper's settings: mu 0.95, N 5, (a,b,c) above, rms_scale 0.2, nesterov 1,
+ * eps 1e-7, lr 0, weight_decay 0. */
+int muon_default_hparams(muon_hparams* hp);
+
+/*
+ * Workspace size for a parameter list.  Only rows/cols/dtypes of `shapes` are read (pointers may be
+ * null).  ns_dtype selects the Newton-Schulz arithmetic: MUON_BF16 (bf16 operands, fp32 accumulation;
+ * section 2.3 notes bf16 suffices) or MUON_F32.  The Newton-Schulz temporaries of all matrices are
+ * kept resident when they fit in `max_bytes`; otherwise the list is processed in consecutive chunks
+ * that reuse the workspace.  max_bytes == 0 means "no limit".  *out receives the number of bytes to
+ * allocate (256-byte aligned device memory); it is never below the minimum that muon_init accepts.
+ */
+int muon_workspace_bytes(const muon_param* shapes, int32_t n, int32_t ns_dtype, size_t max_bytes, size_t* out);
+
+/*
+ * Builds the launch plan (orientation, padded extents, tile tables, chunking) for a parameter list and
+ * uploads its tables into `workspace` (device memory of `workspace_bytes` bytes, owned by the caller,
+ * which must stay alive and untouched until muon_destroy).  Only rows/cols/dtypes are read from
+ * `shapes`.  Uses the current HIP device; synchronises with the device once.  On success *out holds a
+ * context to be released with muon_destroy.
+ */
+int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dtype,
+              void* workspace, size_t workspace_bytes);
+
+/*
+ * One optimizer step over the whole list (same n, shapes and dtypes as at init; buffer pointers may
+ * change between steps).  hip_stream is a hipStream_t (null = default stream).  update_rms_out is
+ * null or a device array of n floats that receives sqrt(mean(O^2)) per matrix, the logging value
+ * returned by Algorithm 1.  Asynchronous: returns after enqueueing.  W and M are updated in place,
+ * G is not written.  The only host-side wait happens when the pointer list differs from the previous
+ * step's (a small table is then re-uploaded through pinned memory).
+ */
+int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hparams* hp,
+              void* hip_stream, float* update_rms_out);
+
+/*
+ * Test hook: copies O_t of matrix `index`, as left by the last muon_step, into dst (device, rows x cols,
+ * row-major, dtype dst_dtype), in W's orientation.  Enqueued on hip_stream.  Fails with
+ * MUON_E_NOT_RESIDENT when the list is processed in chunks and the matrix is not in the last one.
+ */
+int muon_debug_read_update(muon_ctx* ctx, int32_t index, void* dst, int32_t dst_dtype, void* hip_stream);
+
+/*
+ * Plan introspection (host only, no device work): writes up to `cap` int64 values describing matrix
+ * `index`: {m, n, transposed, m_pad, n_pad, chunk, tile_m, tile_n}.  Returns the number written or
+ * a negative status.
+ */
+int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t cap);
+
+/* Number of chunks the list is processed in (1 = everything resident). */
+int muon_plan_chunks(const muon_ctx* ctx);
+
+/* Releases host-side state.  The workspace is the caller's to free afterwards. */
+void muon_destroy(muon_ctx* ctx);
+
+/* Static, human-readable name of a status code. */
+const char* muon_status_string(int status);
+
+/* The hipError_t (as int) recorded by the last call on this thread that returned MUON_E_HIP. */
+int muon_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MUON_H_ */

@@ -1,0 +1,228 @@
+"""ctypes binding of the C ABI declared in include/muon.h.
+
+Argument marshalling only: every arithmetic step of the Muon update runs inside the
+HIP library.  PyTorch is used by callers for device memory and streams; this module
+touches tensors only to read ``data_ptr()`` / shape / dtype.
+
+The library is loaded from the package directory (built in-tree by ``build.py``).
+There is no fallback: a missing library is an ImportError at first use.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Iterable, List, Optional, Sequence
+
+MUON_F32, MUON_BF16 = 0, 1
+MUON_OK = 0
+STATUS_NAMES = {
+    0: "MUON_OK", -1: "MUON_E_INVALID_ARG", -2: "MUON_E_UNSUPPORTED_DTYPE", -3: "MUON_E_SHAPE_MISMATCH",
+    -4: "MUON_E_WORKSPACE_TOO_SMALL", -5: "MUON_E_HIP", -6: "MUON_E_NOT_RESIDENT", -7: "MUON_E_MISALIGNED",
+}
+
+EXPORTS = (
+    "muon_default_hparams", "muon_workspace_bytes", "muon_init", "muon_step", "muon_debug_read_update",
+    "muon_plan_describe", "muon_plan_chunks", "muon_destroy", "muon_status_string", "muon_last_hip_error",
+)
+
+
+class muon_param(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p),
+                ("rows", C.c_int64), ("cols", C.c_int64), ("w_dtype", C.c_int32), ("g_dtype", C.c_int32)]
+
+
+class muon_hparams(C.Structure):
+    _fields_ = [("lr", C.c_double), ("weight_decay", C.c_double), ("momentum", C.c_double),
+                ("a", C.c_double), ("b", C.c_double), ("c", C.c_double),
+                ("rms_scale", C.c_double), ("eps", C.c_double),
+                ("ns_steps", C.c_int32), ("nesterov", C.c_int32)]
+
+
+class MuonError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = f"{where}: {STATUS_NAMES.get(status, status)}"
+        try:
+            msg += f" ({lib().muon_status_string(status).decode()})"
+            if status == -5:
+                msg += f" hipError={lib().muon_last_hip_error()}"
+        except Exception:  # pragma: no cover
+            pass
+        super().__init__(msg)
+
+
+_LIB = None
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmuon_hip.so")
+
+
+def lib() -> C.CDLL:
+    """Loads the HIP library (once).  Raises ImportError when it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2502_16982_amd.build` "
+                          "(there is no CPU fallback)")
+    L = C.CDLL(path)
+    P = C.POINTER
+    L.muon_default_hparams.argtypes = [P(muon_hparams)]
+    L.muon_default_hparams.restype = C.c_int
+    L.muon_workspace_bytes.argtypes = [P(muon_param), C.c_int32, C.c_int32, C.c_size_t, P(C.c_size_t)]
+    L.muon_workspace_bytes.restype = C.c_int
+    L.muon_init.argtypes = [P(C.c_void_p), P(muon_param), C.c_int32, C.c_int32, C.c_void_p, C.c_size_t]
+    L.muon_init.restype = C.c_int
+    L.muon_step.argtypes = [C.c_void_p, P(muon_param), C.c_int32, P(muon_hparams), C.c_void_p, C.c_void_p]
+    L.muon_step.restype = C.c_int
+    L.muon_debug_read_update.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    L.muon_debug_read_update.restype = C.c_int
+    L.muon_plan_describe.argtypes = [C.c_void_p, C.c_int32, P(C.c_int64), C.c_int32]
+    L.muon_plan_describe.restype = C.c_int
+    L.muon_plan_chunks.argtypes = [C.c_void_p]
+    L.muon_plan_chunks.restype = C.c_int
+    L.muon_destroy.argtypes = [C.c_void_p]
+    L.muon_destroy.restype = None
+    L.muon_status_string.argtypes = [C.c_int]
+    L.muon_status_string.restype = C.c_char_p
+    L.muon_last_hip_error.argtypes = []
+    L.muon_last_hip_error.restype = C.c_int
+    _LIB = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != MUON_OK:
+        raise MuonError(status, where)
+
+
+def dtype_code(torch_dtype) -> int:
+    import torch
+    if torch_dtype == torch.float32:
+        return MUON_F32
+    if torch_dtype == torch.bfloat16:
+        return MUON_BF16
+    raise MuonError(-2, f"dtype {torch_dtype}")
+
+
+def default_hparams(**overrides) -> muon_hparams:
+    hp = muon_hparams()
+    _check(lib().muon_default_hparams(C.byref(hp)), "muon_default_hparams")
+    for k, v in overrides.items():
+        if not hasattr(hp, k):
+            raise AttributeError(k)
+        setattr(hp, k, v)
+    return hp
+
+
+def param_array(shapes: Sequence[Sequence[int]], w_dtypes: Sequence[int], g_dtypes: Sequence[int]):
+    arr = (muon_param * len(shapes))()
+    for i, (r, c) in enumerate(shapes):
+        arr[i].rows, arr[i].cols = int(r), int(c)
+        arr[i].w_dtype, arr[i].g_dtype = int(w_dtypes[i]), int(g_dtypes[i])
+    return arr
+
+
+def muon_workspace_bytes(params, n: int, ns_dtype: int, max_bytes: int = 0) -> int:
+    out = C.c_size_t(0)
+    _check(lib().muon_workspace_bytes(params, n, ns_dtype, max_bytes, C.byref(out)), "muon_workspace_bytes")
+    return int(out.value)
+
+
+def muon_init(params, n: int, ns_dtype: int, workspace_ptr: int, workspace_bytes: int) -> C.c_void_p:
+    ctx = C.c_void_p(None)
+    _check(lib().muon_init(C.byref(ctx), params, n, ns_dtype, C.c_void_p(workspace_ptr), workspace_bytes), "muon_init")
+    return ctx
+
+
+def muon_step(ctx, params, n: int, hp: muon_hparams, stream_ptr: int = 0, update_rms_ptr: int = 0) -> None:
+    _check(lib().muon_step(ctx, params, n, C.byref(hp), C.c_void_p(stream_ptr), C.c_void_p(update_rms_ptr)), "muon_step")
+
+
+def muon_debug_read_update(ctx, index: int, dst_ptr: int, dst_dtype: int, stream_ptr: int = 0) -> None:
+    _check(lib().muon_debug_read_update(ctx, index, C.c_void_p(dst_ptr), dst_dtype, C.c_void_p(stream_ptr)),
+           "muon_debug_read_update")
+
+
+def muon_plan_describe(ctx, index: int) -> dict:
+    buf = (C.c_int64 * 8)()
+    k = lib().muon_plan_describe(ctx, index, buf, 8)
+    if k < 0:
+        raise MuonError(k, "muon_plan_describe")
+    keys = ("m", "n", "transposed", "m_pad", "n_pad", "chunk", "tile_m", "tile_n")
+    return dict(zip(keys, [int(v) for v in buf[:k]]))
+
+
+def muon_plan_chunks(ctx) -> int:
+    k = lib().muon_plan_chunks(ctx)
+    if k < 0:
+        raise MuonError(k, "muon_plan_chunks")
+    return k
+
+
+def muon_destroy(ctx) -> None:
+    lib().muon_destroy(ctx)
+
+
+class MuonStepper:
+    """Convenience holder: one context + workspace for a fixed list of (W, G, M) torch tensors.
+
+    Marshals pointers and calls the C ABI; owns the workspace tensor.
+    """
+
+    def __init__(self, tensors: Iterable[tuple], ns_dtype: str = "bf16", max_workspace_bytes: int = 0):
+        import torch
+        self.tensors: List[tuple] = [tuple(t) for t in tensors]
+        if not self.tensors:
+            raise MuonError(-1, "empty parameter list")
+        self.ns_dtype = MUON_BF16 if ns_dtype == "bf16" else MUON_F32
+        self.n = len(self.tensors)
+        self.params = (muon_param * self.n)()
+        self.device = self.tensors[0][0].device
+        self.set_tensors(self.tensors)
+        nbytes = muon_workspace_bytes(self.params, self.n, self.ns_dtype, max_workspace_bytes)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.workspace_bytes = nbytes
+        self.ctx = muon_init(self.params, self.n, self.ns_dtype, self.workspace.data_ptr(), nbytes)
+
+    def set_tensors(self, tensors) -> None:
+        self.tensors = [tuple(t) for t in tensors]
+        for i, (w, g, m) in enumerate(self.tensors):
+            if w.dim() != 2 or g.shape != w.shape or m.shape != w.shape:
+                raise MuonError(-1, f"matrix {i}: W, G, M must be 2-D and of one shape")
+            if not (w.is_contiguous() and g.is_contiguous() and m.is_contiguous()):
+                raise MuonError(-1, f"matrix {i}: buffers must be contiguous")
+            p = self.params[i]
+            p.w, p.g, p.m = w.data_ptr(), g.data_ptr(), m.data_ptr()
+            p.rows, p.cols = w.shape
+            p.w_dtype, p.g_dtype = dtype_code(w.dtype), dtype_code(g.dtype)
+            if dtype_code(m.dtype) != MUON_F32:
+                raise MuonError(-2, f"matrix {i}: momentum must be fp32")
+
+    def step(self, hp: muon_hparams, stream=None, update_rms=None) -> None:
+        import torch
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        muon_step(self.ctx, self.params, self.n, hp, s.cuda_stream,
+                  0 if update_rms is None else update_rms.data_ptr())
+
+    def read_update(self, index: int, dtype=None):
+        import torch
+        w = self.tensors[index][0]
+        dtype = dtype or torch.float32
+        out = torch.empty(w.shape, dtype=dtype, device=self.device)
+        muon_debug_read_update(self.ctx, index, out.data_ptr(), dtype_code(dtype),
+                               torch.cuda.current_stream(self.device).cuda_stream)
+        return out
+
+    def close(self) -> None:
+        if getattr(self, "ctx", None) is not None:
+            muon_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):  # pragma: no cover
+        try:
+            self.close()
+        except Exception:
+            pass

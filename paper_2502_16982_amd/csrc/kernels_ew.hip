@@ -1,0 +1,345 @@
+// HBM-bound kernels of the Muon step for gfx950: momentum + Frobenius partials + cast/orient,
+// norm finalisation, the scaled weight-decayed apply, update-RMS and a test read-back.
+//
+// All of them walk a table of 64x64 element tiles so that one launch covers every matrix of a chunk.
+#include <hip/hip_runtime.h>
+
+#include "muon_launch.h"
+
+namespace muon {
+namespace {
+
+typedef unsigned short u16;
+
+__device__ __forceinline__ float bf16_to_f32(u16 h) { return __uint_as_float(((unsigned)h) << 16); }
+
+// round-to-nearest-even, NaN kept quiet
+__device__ __forceinline__ u16 f32_to_bf16(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u16)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (u16)(u >> 16);
+}
+
+__device__ __forceinline__ unsigned pack2(float lo, float hi) {
+  return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+}
+
+// Deterministic block-wide sum (256 threads): butterfly inside each wave, then the 4 wave sums in order.
+__device__ __forceinline__ float block_sum_256(float v, float* red /* >= 4 floats of LDS */) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+template <typename T>
+__device__ __forceinline__ void load16(const T* p, float* out);
+template <>
+__device__ __forceinline__ void load16<float>(const float* p, float* out) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float4 v = reinterpret_cast<const float4*>(p)[i];
+    out[4 * i + 0] = v.x; out[4 * i + 1] = v.y; out[4 * i + 2] = v.z; out[4 * i + 3] = v.w;
+  }
+}
+template <>
+__device__ __forceinline__ void load16<u16>(const u16* p, float* out) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      out[8 * i + 2 * j] = __uint_as_float(w[j] << 16);
+      out[8 * i + 2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+    }
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ void store16(T* p, const float* in);
+template <>
+__device__ __forceinline__ void store16<float>(float* p, const float* in) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    reinterpret_cast<float4*>(p)[i] = make_float4(in[4 * i], in[4 * i + 1], in[4 * i + 2], in[4 * i + 3]);
+}
+template <>
+__device__ __forceinline__ void store16<u16>(u16* p, const float* in) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    reinterpret_cast<uint4*>(p)[i] = make_uint4(pack2(in[8 * i], in[8 * i + 1]), pack2(in[8 * i + 2], in[8 * i + 3]),
+                                                pack2(in[8 * i + 4], in[8 * i + 5]), pack2(in[8 * i + 6], in[8 * i + 7]));
+}
+
+template <typename T>
+__device__ __forceinline__ float load1(const T* p);
+template <>
+__device__ __forceinline__ float load1<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load1<u16>(const u16* p) { return bf16_to_f32(*p); }
+template <typename T>
+__device__ __forceinline__ void store1(T* p, float v);
+template <>
+__device__ __forceinline__ void store1<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store1<u16>(u16* p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ------------------------------------------------------------------------------------------------------
+// a1 + a2 (first stage) + a3.  Thread t of a block owns row t/4 and 16 consecutive columns of a 64x64 tile
+// in U's orientation.  GT: gradient element type; XT: Newton-Schulz element type.
+// Writes: M (guarded), the tile of U into the buffer of the same orientation, the transposed tile (through
+// LDS) into the buffer of the other orientation, both zero-filled outside A x B, and one partial sum of U^2.
+// ------------------------------------------------------------------------------------------------------
+template <typename GT, typename XT>
+__device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float mu, int nesterov,
+                                              float (*lds)[kEwTile + 1], float* red) {
+  const int tid = threadIdx.x;
+  const int r = tr * kEwTile + (tid >> 2);
+  const int c0 = tc * kEwTile + (tid & 3) * 16;
+  const int A = d.rows, B = d.cols;
+  const GT* g = static_cast<const GT*>(pt.g);
+  float* m = pt.m;
+
+  float u[16];
+  float ss = 0.f;
+  const bool row_ok = r < A;
+  const size_t base = (size_t)r * (size_t)B + (size_t)c0;
+  const bool fast = row_ok && (c0 + 16 <= B) && ((B & 7) == 0) && aligned16(m) && aligned16(g);
+  if (fast) {
+    float mv[16], gv[16];
+    load16<float>(m + base, mv);
+    load16<GT>(g + base, gv);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float mn = fmaf(mu, mv[i], gv[i]);
+      mv[i] = mn;
+      u[i] = nesterov ? fmaf(mu, mn, gv[i]) : mn;
+      ss = fmaf(u[i], u[i], ss);
+    }
+    store16<float>(m + base, mv);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float ui = 0.f;
+      if (row_ok && c0 + i < B) {
+        const float gi = load1<GT>(g + base + i);
+        const float mn = fmaf(mu, m[base + i], gi);
+        m[base + i] = mn;
+        ui = nesterov ? fmaf(mu, mn, gi) : mn;
+      }
+      u[i] = ui;
+      ss = fmaf(ui, ui, ss);
+    }
+  }
+
+  // Orientation: the buffer whose rows run along U's rows, and the one holding U^T.
+  // not transposed: X = U (pitch np), Xt = U^T (pitch mp).  transposed: Xt = U (pitch mp), X = U^T (pitch np).
+  XT* same = static_cast<XT*>(d.transposed ? d.Xt[0] : d.X);
+  XT* flip = static_cast<XT*>(d.transposed ? d.X : d.Xt[0]);
+  const int pitch_same = d.transposed ? d.mp : d.np;
+  const int pitch_flip = d.transposed ? d.np : d.mp;
+
+  store16<XT>(same + (size_t)r * pitch_same + c0, u);
+
+  const int lr_ = tid >> 2, lc0 = (tid & 3) * 16;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) lds[lc0 + i][lr_] = u[i];
+  const float total = block_sum_256(ss, red);   // contains the barrier that publishes the LDS tile
+  float t[16];
+  const int fc = tid >> 2, fr0 = (tid & 3) * 16;   // row of U^T (= column of U), 16 consecutive columns of U^T
+#pragma unroll
+  for (int i = 0; i < 16; ++i) t[i] = lds[fc][fr0 + i];
+  store16<XT>(flip + (size_t)(tc * kEwTile + fc) * pitch_flip + tr * kEwTile + fr0, t);
+
+  if (tid == 0) d.partials[tr * d.ew_tiles_c + tc] = total;
+}
+
+template <typename XT>
+__global__ __launch_bounds__(256) void momentum_norm_cast_kernel(const MatDesc* __restrict__ mats,
+                                                                  const MatPtrs* __restrict__ ptrs,
+                                                                  const EwTile* __restrict__ tiles, float mu,
+                                                                  int nesterov) {
+  __shared__ float lds[kEwTile][kEwTile + 1];
+  __shared__ float red[4];
+  const EwTile t = tiles[blockIdx.x];
+  const MatDesc d = mats[t.mat];
+  const MatPtrs pt = ptrs[t.mat];
+  if (d.g_dtype == kDtypeBF16)
+    momentum_tile<u16, XT>(d, pt, t.tr, t.tc, mu, nesterov, lds, red);
+  else
+    momentum_tile<float, XT>(d, pt, t.tr, t.tc, mu, nesterov, lds, red);
+}
+
+// ------------------------------------------------------------------------------------------------------
+// a2 second stage: one block per matrix sums its partials in a fixed order, in double.
+// ------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void norm_finalize_kernel(const MatDesc* __restrict__ mats, int first_mat, double eps) {
+  __shared__ double red[256];
+  const MatDesc d = mats[first_mat + blockIdx.x];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < d.n_part; i += 256) acc += (double)d.partials[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double inv = 1.0 / (sqrt(red[0]) + eps);
+    // an all-zero U with eps = 0 would give inf; X is all zero then, and 0 * inf must not appear
+    const float s = (red[0] > 0.0 || eps > 0.0) ? (float)inv : 0.f;
+    d.scal[0] = s;
+    d.scal[1] = (red[0] > 0.0 || eps > 0.0) ? (float)(inv * inv) : 0.f;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------------
+// a8: W <- W - lr * (rms_scale*sqrt(max(A,B)) * O + wd * W), fp32 math, one rounding to W's dtype.
+// ------------------------------------------------------------------------------------------------------
+template <typename WT, typename XT>
+__device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float lr, float wd,
+                                           float scale, int o_sel, float* red) {
+  const int tid = threadIdx.x;
+  const int r = tr * kEwTile + (tid >> 2);
+  const int c0 = tc * kEwTile + (tid & 3) * 16;
+  const int A = d.rows, B = d.cols;
+  WT* w = static_cast<WT*>(pt.w);
+  const XT* o = static_cast<const XT*>(d.transposed ? d.Xt[o_sel] : d.X);
+  const int pitch = d.transposed ? d.mp : d.np;
+  float ss = 0.f;
+  if (r < A && c0 < B) {
+    const size_t base = (size_t)r * (size_t)B + (size_t)c0;
+    const XT* op = o + (size_t)r * pitch + c0;
+    if ((c0 + 16 <= B) && ((B & 7) == 0) && aligned16(w)) {
+      float wv[16], ov[16];
+      load16<WT>(w + base, wv);
+      load16<XT>(op, ov);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        ss = fmaf(ov[i], ov[i], ss);
+        const float t = fmaf(wd, wv[i], scale * ov[i]);
+        wv[i] = fmaf(-lr, t, wv[i]);
+      }
+      store16<WT>(w + base, wv);
+    } else {
+      for (int i = 0; i < 16 && c0 + i < B; ++i) {
+        const float ov = load1<XT>(op + i);
+        const float wv = load1<WT>(w + base + i);
+        ss = fmaf(ov, ov, ss);
+        const float t = fmaf(wd, wv, scale * ov);
+        store1<WT>(w + base + i, fmaf(-lr, t, wv));
+      }
+    }
+  }
+  const float total = block_sum_256(ss, red);
+  if (tid == 0) d.partials[tr * d.ew_tiles_c + tc] = total;
+}
+
+template <typename XT>
+__global__ __launch_bounds__(256) void apply_update_kernel(const MatDesc* __restrict__ mats, const MatPtrs* __restrict__ ptrs,
+                                                            const EwTile* __restrict__ tiles, float lr, float wd,
+                                                            float rms_scale, int o_sel, int use_s) {
+  __shared__ float red[4];
+  const EwTile t = tiles[blockIdx.x];
+  const MatDesc d = mats[t.mat];
+  const MatPtrs pt = ptrs[t.mat];
+  float scale = rms_scale * d.sqrt_max;
+  if (use_s) scale *= d.scal[0];
+  if (d.w_dtype == kDtypeBF16)
+    apply_tile<u16, XT>(d, pt, t.tr, t.tc, lr, wd, scale, o_sel, red);
+  else
+    apply_tile<float, XT>(d, pt, t.tr, t.tc, lr, wd, scale, o_sel, red);
+}
+
+// sqrt(mean(O^2)) per matrix from the per-tile sums left by apply_update_kernel.
+__global__ __launch_bounds__(256) void update_rms_kernel(const MatDesc* __restrict__ mats, int first_mat, int use_s,
+                                                          float* __restrict__ out) {
+  __shared__ double red[256];
+  const MatDesc d = mats[first_mat + blockIdx.x];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < d.n_part; i += 256) acc += (double)d.partials[i];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    double rms = sqrt(red[0] / ((double)d.rows * (double)d.cols));
+    if (use_s) rms *= (double)d.scal[0];
+    out[first_mat + blockIdx.x] = (float)rms;
+  }
+}
+
+template <typename XT, typename DT>
+__global__ __launch_bounds__(256) void read_update_kernel(const MatDesc* __restrict__ mats, int mat, int o_sel, int use_s,
+                                                           DT* __restrict__ dst) {
+  const MatDesc d = mats[mat];
+  const XT* o = static_cast<const XT*>(d.transposed ? d.Xt[o_sel] : d.X);
+  const int pitch = d.transposed ? d.mp : d.np;
+  const float s = use_s ? d.scal[0] : 1.f;
+  const size_t total = (size_t)d.rows * (size_t)d.cols;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const size_t r = i / (size_t)d.cols, c = i % (size_t)d.cols;
+    store1<DT>(dst + i, s * load1<XT>(o + r * pitch + c));
+  }
+}
+
+}  // namespace
+
+hipError_t launch_momentum_norm_cast(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles, float mu,
+                                     int nesterov, int ns_dtype, hipStream_t s) {
+  if (n_tiles <= 0) return hipSuccess;
+  if (ns_dtype == kDtypeBF16)
+    momentum_norm_cast_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov);
+  else
+    momentum_norm_cast_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, double eps, hipStream_t s) {
+  if (n_mats <= 0) return hipSuccess;
+  norm_finalize_kernel<<<n_mats, 256, 0, s>>>(mats, first_mat, eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_apply_update(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles, float lr, float wd,
+                               float rms_scale, int o_sel, int use_s, int ns_dtype, hipStream_t s) {
+  if (n_tiles <= 0) return hipSuccess;
+  if (ns_dtype == kDtypeBF16)
+    apply_update_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, o_sel, use_s);
+  else
+    apply_update_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, o_sel, use_s);
+  return hipGetLastError();
+}
+
+hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int use_s, float* out, hipStream_t s) {
+  if (n_mats <= 0) return hipSuccess;
+  update_rms_kernel<<<n_mats, 256, 0, s>>>(mats, first_mat, use_s, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_read_update(const MatDesc* mats, int mat, int o_sel, int use_s, int ns_dtype, void* dst, int dst_dtype,
+                              hipStream_t s) {
+  const int grid = 1024;
+  if (ns_dtype == kDtypeBF16) {
+    if (dst_dtype == kDtypeBF16)
+      read_update_kernel<u16, u16><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<u16*>(dst));
+    else
+      read_update_kernel<u16, float><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<float*>(dst));
+  } else {
+    if (dst_dtype == kDtypeBF16)
+      read_update_kernel<float, u16><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<u16*>(dst));
+    else
+      read_update_kernel<float, float><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<float*>(dst));
+  }
+  return hipGetLastError();
+}
+
+}  // namespace muon

@@ -1,0 +1,520 @@
+// C ABI and host-side planner of the MI355X Muon step (see include/muon.h for the contract).
+//
+// muon_init turns a list of matrix shapes into: the orientation and padded extents of every matrix, the
+// chunking of the list against the workspace, and device tables (matrix records, elementwise tiles, one
+// grouped-GEMM problem table and tile table per Newton-Schulz product).  muon_step only enqueues kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/muon.h"
+#include "muon_launch.h"
+
+using namespace muon;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_fail(hipError_t e) {
+  g_last_hip_error = (int)e;
+  return MUON_E_HIP;
+}
+#define MUON_HIP(expr)                          \
+  do {                                          \
+    hipError_t e__ = (expr);                    \
+    if (e__ != hipSuccess) return hip_fail(e__); \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int round_up_i(int64_t v, int a) { return (int)((v + a - 1) / a * a); }
+
+constexpr int64_t kMaxDim = 1 << 20;   // tile indices are 16-bit in units of >= 64 elements
+
+struct MatPlan {
+  int64_t rows, cols;
+  int m, n, mp, np, transposed;
+  int w_dtype, g_dtype;
+  int shape;        // GemmShape (bf16) or 0 (fp32)
+  int tile;         // GEMM block tile in elements
+  int chunk;
+  int ew_tr, ew_tc; // 64x64 tiles in U's orientation (padded)
+  size_t ns_bytes;  // X + 2 Xt + Ag + Bp
+  size_t part_off;  // first partial (floats)
+};
+
+// Launch group: the matrices of one chunk that share a GEMM block tile.
+struct Group {
+  int shape;
+  int n_prob;
+  size_t prob_gram, prob_poly, prob_apply[4];  // byte offsets of the problem tables in the table region
+  size_t tiles_sym, tiles_apply;               // byte offsets of the tile tables
+  int n_tiles_sym, n_tiles_apply;
+};
+
+struct Chunk {
+  int first, count;
+  size_t ew_tiles_off;   // byte offset of the EwTile table
+  int n_ew_tiles;
+  std::vector<Group> groups;
+};
+
+// GEMM block tile for a matrix.  256x256 tiles halve the LDS traffic per flop but need dimensions that are
+// whole multiples of 256 to avoid padding waste, and enough tiles to fill 256 compute units.
+int pick_shape(int m, int n) {
+  if (m % 256 == 0 && n % 256 == 0 && m >= 1024) return kShape256;
+  return kShape128;
+}
+
+int validate_shapes(const muon_param* p, int32_t n, int32_t ns_dtype) {
+  if (!p || n <= 0) return MUON_E_INVALID_ARG;
+  if (ns_dtype != MUON_F32 && ns_dtype != MUON_BF16) return MUON_E_UNSUPPORTED_DTYPE;
+  for (int i = 0; i < n; ++i) {
+    if (p[i].rows < 1 || p[i].cols < 1 || p[i].rows > kMaxDim || p[i].cols > kMaxDim) return MUON_E_INVALID_ARG;
+    if ((p[i].w_dtype != MUON_F32 && p[i].w_dtype != MUON_BF16) || (p[i].g_dtype != MUON_F32 && p[i].g_dtype != MUON_BF16))
+      return MUON_E_UNSUPPORTED_DTYPE;
+  }
+  return MUON_OK;
+}
+
+void plan_matrices(const muon_param* p, int n, int ns_dtype, std::vector<MatPlan>& out, size_t& total_partials) {
+  out.resize(n);
+  total_partials = 0;
+  const size_t es = ns_dtype == MUON_BF16 ? 2 : 4;
+  for (int i = 0; i < n; ++i) {
+    MatPlan& q = out[i];
+    q.rows = p[i].rows;
+    q.cols = p[i].cols;
+    q.transposed = q.rows > q.cols;
+    q.m = (int)std::min(q.rows, q.cols);
+    q.n = (int)std::max(q.rows, q.cols);
+    q.w_dtype = p[i].w_dtype;
+    q.g_dtype = p[i].g_dtype;
+    if (ns_dtype == MUON_BF16) {
+      q.shape = pick_shape(q.m, q.n);
+      q.tile = kShapeTile[q.shape];
+    } else {
+      q.shape = 0;
+      q.tile = kF32Tile;
+    }
+    q.mp = round_up_i(q.m, q.tile);
+    q.np = round_up_i(q.n, q.tile);
+    const int ap = q.transposed ? q.np : q.mp, bp = q.transposed ? q.mp : q.np;
+    q.ew_tr = ap / kEwTile;
+    q.ew_tc = bp / kEwTile;
+    q.ns_bytes = align_up(es * (size_t)q.mp * q.np, 256) * 3 + align_up(es * (size_t)q.mp * q.mp, 256) * 2;
+    q.part_off = total_partials;
+    total_partials += (size_t)q.ew_tr * q.ew_tc;
+    q.chunk = 0;
+  }
+}
+
+// Size of everything that is not Newton-Schulz temporaries, for a given chunking.
+struct TableLayout {
+  size_t mats, ptrs, scal, partials, ew_tiles, gemm, total;
+};
+
+size_t gemm_tables_bytes_for(const MatPlan& q) {
+  const int tm = q.mp / q.tile, tn = q.np / q.tile;
+  const size_t sym = (size_t)tm * (tm + 1) / 2, app = (size_t)tm * tn;
+  return 6 * sizeof(GemmProblem) + (sym + app) * sizeof(GemmTile);
+}
+
+TableLayout table_layout(const std::vector<MatPlan>& mp, size_t total_partials) {
+  TableLayout t{};
+  const size_t n = mp.size();
+  size_t gemm = 0;
+  for (const MatPlan& q : mp) gemm += gemm_tables_bytes_for(q);
+  // every table start is aligned to 256 B; chunks x groups x 8 tables bounds the slack
+  t.mats = align_up(n * sizeof(MatDesc), 256);
+  t.ptrs = align_up(n * sizeof(MatPtrs), 256);
+  t.scal = align_up(n * 4 * sizeof(float), 256);
+  t.partials = align_up(total_partials * sizeof(float), 256);
+  t.ew_tiles = align_up(total_partials * sizeof(EwTile), 256) + 256 * n;  // per-chunk alignment slack
+  t.gemm = align_up(gemm, 256) + (size_t)n * 16 * 256;                                     // alignment slack: <= 2 groups x 8 tables per chunk
+  t.total = t.mats + t.ptrs + t.scal + t.partials + t.ew_tiles + t.gemm;
+  return t;
+}
+
+}  // namespace
+
+struct muon_ctx {
+  int n = 0;
+  int ns_dtype = MUON_BF16;
+  int device = 0;
+  std::vector<MatPlan> mats;
+  std::vector<Chunk> chunks;
+  unsigned char* ws = nullptr;
+  size_t ws_bytes = 0;
+  // device tables
+  MatDesc* d_mats = nullptr;
+  MatPtrs* d_ptrs = nullptr;
+  // dynamic pointer upload
+  MatPtrs* h_ptrs_pinned = nullptr;
+  std::vector<MatPtrs> last_ptrs;
+  bool ptrs_valid = false;
+  hipEvent_t upload_done = nullptr;
+  // state of the last step, for the debug read
+  int last_o_sel = 0, last_use_s = 0, last_chunk = -1;
+};
+
+extern "C" {
+
+int muon_default_hparams(muon_hparams* hp) {
+  if (!hp) return MUON_E_INVALID_ARG;
+  hp->lr = 0.0;
+  hp->weight_decay = 0.0;
+  hp->momentum = 0.95;
+  hp->a = 3.4445;
+  hp->b = -4.7750;
+  hp->c = 2.0315;
+  hp->rms_scale = 0.2;
+  hp->eps = 1e-7;
+  hp->ns_steps = 5;
+  hp->nesterov = 1;
+  return MUON_OK;
+}
+
+int muon_workspace_bytes(const muon_param* shapes, int32_t n, int32_t ns_dtype, size_t max_bytes, size_t* out) {
+  if (!out) return MUON_E_INVALID_ARG;
+  int st = validate_shapes(shapes, n, ns_dtype);
+  if (st != MUON_OK) return st;
+  std::vector<MatPlan> mp;
+  size_t total_partials = 0;
+  plan_matrices(shapes, n, ns_dtype, mp, total_partials);
+  const TableLayout tl = table_layout(mp, total_partials);
+  size_t all = 0, biggest = 0;
+  for (const MatPlan& q : mp) {
+    all += q.ns_bytes;
+    biggest = std::max(biggest, q.ns_bytes);
+  }
+  size_t want = tl.total + all;
+  const size_t least = tl.total + biggest;
+  if (max_bytes != 0 && want > max_bytes) want = std::max(max_bytes, least);
+  *out = align_up(want, 256);
+  return MUON_OK;
+}
+
+int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dtype, void* workspace,
+              size_t workspace_bytes) {
+  if (!out) return MUON_E_INVALID_ARG;
+  *out = nullptr;
+  int st = validate_shapes(shapes, n, ns_dtype);
+  if (st != MUON_OK) return st;
+  if (!workspace) return MUON_E_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MUON_E_MISALIGNED;
+
+  muon_ctx* ctx = new (std::nothrow) muon_ctx();
+  if (!ctx) return MUON_E_INVALID_ARG;
+  ctx->n = n;
+  ctx->ns_dtype = ns_dtype;
+  ctx->ws = static_cast<unsigned char*>(workspace);
+  ctx->ws_bytes = workspace_bytes;
+  size_t total_partials = 0;
+  plan_matrices(shapes, n, ns_dtype, ctx->mats, total_partials);
+  const TableLayout tl = table_layout(ctx->mats, total_partials);
+
+  size_t biggest = 0;
+  for (const MatPlan& q : ctx->mats) biggest = std::max(biggest, q.ns_bytes);
+  if (workspace_bytes < tl.total + biggest) {
+    delete ctx;
+    return MUON_E_WORKSPACE_TOO_SMALL;
+  }
+  const size_t ns_budget = workspace_bytes - tl.total;
+
+  // ---- chunking: consecutive matrices while their temporaries fit ----
+  {
+    size_t used = 0;
+    Chunk cur{};
+    cur.first = 0;
+    for (int i = 0; i < n; ++i) {
+      if (cur.count > 0 && used + ctx->mats[i].ns_bytes > ns_budget) {
+        ctx->chunks.push_back(cur);
+        cur = Chunk{};
+        cur.first = i;
+        used = 0;
+      }
+      ctx->mats[i].chunk = (int)ctx->chunks.size();
+      used += ctx->mats[i].ns_bytes;
+      cur.count++;
+    }
+    ctx->chunks.push_back(cur);
+  }
+
+  // ---- host image of the table region ----
+  std::vector<unsigned char> img(tl.total, 0);
+  size_t off = 0;
+  const size_t off_mats = off; off += tl.mats;
+  const size_t off_ptrs = off; off += tl.ptrs;
+  const size_t off_scal = off; off += tl.scal;
+  const size_t off_part = off; off += tl.partials;
+  size_t cursor = off;   // ew tiles and gemm tables are appended from here
+  unsigned char* ns_base = ctx->ws + tl.total;
+  const size_t es = ns_dtype == MUON_BF16 ? 2 : 4;
+
+  MatDesc* h_mats = reinterpret_cast<MatDesc*>(img.data() + off_mats);
+  auto dev = [&](size_t o) { return ctx->ws + o; };
+
+  for (Chunk& ch : ctx->chunks) {
+    size_t ns_off = 0;
+    for (int i = ch.first; i < ch.first + ch.count; ++i) {
+      const MatPlan& q = ctx->mats[i];
+      MatDesc& d = h_mats[i];
+      const size_t xb = align_up(es * (size_t)q.mp * q.np, 256), ab = align_up(es * (size_t)q.mp * q.mp, 256);
+      d.X = ns_base + ns_off; ns_off += xb;
+      d.Xt[0] = ns_base + ns_off; ns_off += xb;
+      d.Xt[1] = ns_base + ns_off; ns_off += xb;
+      d.Ag = ns_base + ns_off; ns_off += ab;
+      d.Bp = ns_base + ns_off; ns_off += ab;
+      d.partials = reinterpret_cast<float*>(dev(off_part)) + q.part_off;
+      d.scal = reinterpret_cast<float*>(dev(off_scal)) + 4 * (size_t)i;
+      d.rows = (int)q.rows; d.cols = (int)q.cols;
+      d.m = q.m; d.n = q.n; d.mp = q.mp; d.np = q.np;
+      d.transposed = q.transposed;
+      d.w_dtype = q.w_dtype; d.g_dtype = q.g_dtype;
+      d.n_part = q.ew_tr * q.ew_tc;
+      d.ew_tiles_c = q.ew_tc;
+      d.sqrt_max = (float)std::sqrt((double)q.n);
+    }
+
+    // elementwise tiles of the chunk
+    cursor = align_up(cursor, 256);
+    ch.ew_tiles_off = cursor;
+    ch.n_ew_tiles = 0;
+    {
+      EwTile* t = reinterpret_cast<EwTile*>(img.data() + cursor);
+      for (int i = ch.first; i < ch.first + ch.count; ++i) {
+        const MatPlan& q = ctx->mats[i];
+        for (int r = 0; r < q.ew_tr; ++r)
+          for (int c = 0; c < q.ew_tc; ++c) {
+            t[ch.n_ew_tiles].mat = i;
+            t[ch.n_ew_tiles].tr = (int16_t)r;
+            t[ch.n_ew_tiles].tc = (int16_t)c;
+            ch.n_ew_tiles++;
+          }
+      }
+      cursor += (size_t)ch.n_ew_tiles * sizeof(EwTile);
+    }
+
+    // GEMM groups of the chunk
+    const int n_shapes = ns_dtype == MUON_BF16 ? (int)kNumShapes : 1;
+    for (int s = 0; s < n_shapes; ++s) {
+      std::vector<int> members;
+      for (int i = ch.first; i < ch.first + ch.count; ++i)
+        if (ctx->mats[i].shape == s) members.push_back(i);
+      if (members.empty()) continue;
+      // longest work first, so that the tail of the launch is made of short tiles
+      std::stable_sort(members.begin(), members.end(), [&](int x, int y) {
+        const MatPlan &a = ctx->mats[x], &b = ctx->mats[y];
+        return (int64_t)a.np + a.mp > (int64_t)b.np + b.mp;
+      });
+      Group g{};
+      g.shape = s;
+      g.n_prob = (int)members.size();
+      auto take = [&](size_t bytes) {
+        cursor = align_up(cursor, 256);
+        const size_t o = cursor;
+        cursor += bytes;
+        return o;
+      };
+      g.prob_gram = take(sizeof(GemmProblem) * members.size());
+      g.prob_poly = take(sizeof(GemmProblem) * members.size());
+      for (int v = 0; v < 4; ++v) g.prob_apply[v] = take(sizeof(GemmProblem) * members.size());
+      for (size_t k = 0; k < members.size(); ++k) {
+        const MatPlan& q = ctx->mats[members[k]];
+        const MatDesc& d = h_mats[members[k]];
+        GemmProblem gp{};
+        gp.scal = d.scal;
+        // Gram: A = X X^T
+        gp.L = d.X; gp.R = d.X; gp.E = nullptr; gp.C = d.Ag; gp.Ct = nullptr;
+        gp.K = q.np; gp.ldl = q.np; gp.ldr = q.np; gp.lde = 0; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+        reinterpret_cast<GemmProblem*>(img.data() + g.prob_gram)[k] = gp;
+        // polynomial: B = b A + c A A
+        gp.L = d.Ag; gp.R = d.Ag; gp.E = d.Ag; gp.C = d.Bp; gp.Ct = nullptr;
+        gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.mp; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+        reinterpret_cast<GemmProblem*>(img.data() + g.prob_poly)[k] = gp;
+        // apply: X' = a X + B X, reading X^T from Xt[p], writing X in place and X'^T to Xt[p^1];
+        // the last iteration writes only the layout W needs
+        for (int par = 0; par < 2; ++par)
+          for (int last = 0; last < 2; ++last) {
+            gp.L = d.Bp; gp.R = d.Xt[par]; gp.E = d.X; gp.C = d.X; gp.Ct = d.Xt[par ^ 1];
+            gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.np; gp.ldc = q.np; gp.ldct = q.mp; gp.symmetric = 0;
+            if (last) {
+              if (q.transposed) gp.C = nullptr; else gp.Ct = nullptr;
+            }
+            reinterpret_cast<GemmProblem*>(img.data() + g.prob_apply[par * 2 + last])[k] = gp;
+          }
+      }
+      // tile tables
+      size_t n_sym = 0, n_app = 0;
+      for (int i : members) {
+        const MatPlan& q = ctx->mats[i];
+        const size_t tm = q.mp / q.tile, tn = q.np / q.tile;
+        n_sym += tm * (tm + 1) / 2;
+        n_app += tm * tn;
+      }
+      g.tiles_sym = take(n_sym * sizeof(GemmTile));
+      g.tiles_apply = take(n_app * sizeof(GemmTile));
+      GemmTile* ts = reinterpret_cast<GemmTile*>(img.data() + g.tiles_sym);
+      GemmTile* ta = reinterpret_cast<GemmTile*>(img.data() + g.tiles_apply);
+      size_t is = 0, ia = 0;
+      for (size_t k = 0; k < members.size(); ++k) {
+        const MatPlan& q = ctx->mats[members[k]];
+        const int tm = q.mp / q.tile, tn = q.np / q.tile;
+        for (int i = 0; i < tm; ++i)
+          for (int j = i; j < tm; ++j) ts[is++] = GemmTile{(int32_t)k, (int16_t)i, (int16_t)j};
+        for (int i = 0; i < tm; ++i)
+          for (int j = 0; j < tn; ++j) ta[ia++] = GemmTile{(int32_t)k, (int16_t)i, (int16_t)j};
+      }
+      g.n_tiles_sym = (int)n_sym;
+      g.n_tiles_apply = (int)n_app;
+      ch.groups.push_back(g);
+    }
+  }
+  if (cursor > tl.total) {   // the layout bound is conservative; this cannot happen
+    delete ctx;
+    return MUON_E_WORKSPACE_TOO_SMALL;
+  }
+
+  ctx->d_mats = reinterpret_cast<MatDesc*>(dev(off_mats));
+  ctx->d_ptrs = reinterpret_cast<MatPtrs*>(dev(off_ptrs));
+
+  hipError_t e = hipGetDevice(&ctx->device);
+  if (e == hipSuccess) e = gemm_setup();
+  if (e == hipSuccess) e = hipMemcpy(ctx->ws, img.data(), cursor, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_ptrs_pinned), sizeof(MatPtrs) * (size_t)n, hipHostMallocDefault);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->upload_done, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    muon_destroy(ctx);
+    return hip_fail(e);
+  }
+  ctx->last_ptrs.resize(n);
+  *out = ctx;
+  return MUON_OK;
+}
+
+int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hparams* hp, void* hip_stream,
+              float* update_rms_out) {
+  if (!ctx || !params || !hp) return MUON_E_INVALID_ARG;
+  if (n != ctx->n) return MUON_E_SHAPE_MISMATCH;
+  if (hp->ns_steps < 0 || !(hp->eps >= 0.0) || !std::isfinite(hp->lr) || !std::isfinite(hp->weight_decay) ||
+      !std::isfinite(hp->momentum) || !std::isfinite(hp->a) || !std::isfinite(hp->b) || !std::isfinite(hp->c) ||
+      !std::isfinite(hp->rms_scale))
+    return MUON_E_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  bool changed = !ctx->ptrs_valid;
+  for (int i = 0; i < n; ++i) {
+    const muon_param& p = params[i];
+    const MatPlan& q = ctx->mats[i];
+    if (p.rows != q.rows || p.cols != q.cols || p.w_dtype != q.w_dtype || p.g_dtype != q.g_dtype) return MUON_E_SHAPE_MISMATCH;
+    if (!p.w || !p.g || !p.m) return MUON_E_INVALID_ARG;
+    const uintptr_t wa = p.w_dtype == MUON_BF16 ? 1u : 3u, ga = p.g_dtype == MUON_BF16 ? 1u : 3u;
+    if ((reinterpret_cast<uintptr_t>(p.w) & wa) || (reinterpret_cast<uintptr_t>(p.g) & ga) || (reinterpret_cast<uintptr_t>(p.m) & 3u))
+      return MUON_E_MISALIGNED;
+    const MatPtrs& l = ctx->last_ptrs[i];
+    if (l.w != p.w || l.g != p.g || l.m != p.m) changed = true;
+  }
+  if (changed) {
+    // the previous upload may still be reading the pinned staging buffer
+    if (ctx->ptrs_valid) MUON_HIP(hipEventSynchronize(ctx->upload_done));
+    for (int i = 0; i < n; ++i) {
+      ctx->last_ptrs[i] = MatPtrs{params[i].w, params[i].g, params[i].m};
+      ctx->h_ptrs_pinned[i] = ctx->last_ptrs[i];
+    }
+    MUON_HIP(hipMemcpyAsync(ctx->d_ptrs, ctx->h_ptrs_pinned, sizeof(MatPtrs) * (size_t)n, hipMemcpyHostToDevice, s));
+    MUON_HIP(hipEventRecord(ctx->upload_done, s));
+    ctx->ptrs_valid = true;
+  }
+
+  const int N = hp->ns_steps;
+  const int use_s = N == 0;
+  const int o_sel = N & 1;
+  const float a = (float)hp->a, b = (float)hp->b, c = (float)hp->c;
+  const bool bf = ctx->ns_dtype == MUON_BF16;
+
+  for (size_t ci = 0; ci < ctx->chunks.size(); ++ci) {
+    const Chunk& ch = ctx->chunks[ci];
+    const EwTile* ew = reinterpret_cast<const EwTile*>(ctx->ws + ch.ew_tiles_off);
+    MUON_HIP(launch_momentum_norm_cast(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->momentum, hp->nesterov != 0,
+                                       ctx->ns_dtype, s));
+    MUON_HIP(launch_norm_finalize(ctx->d_mats, ch.first, ch.count, hp->eps, s));
+    for (int it = 0; it < N; ++it) {
+      const int first = it == 0, last = it == N - 1, par = it & 1;
+      for (const Group& g : ch.groups) {
+        auto P = [&](size_t o) { return reinterpret_cast<const GemmProblem*>(ctx->ws + o); };
+        auto T = [&](size_t o) { return reinterpret_cast<const GemmTile*>(ctx->ws + o); };
+        if (bf) {
+          MUON_HIP(launch_gemm_bf16(g.shape, P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
+          MUON_HIP(launch_gemm_bf16(g.shape, P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
+          MUON_HIP(launch_gemm_bf16(g.shape, P(g.prob_apply[par * 2 + last]), T(g.tiles_apply), g.n_tiles_apply, 1.f, a,
+                                    first ? 0 : -1, s));
+        } else {
+          MUON_HIP(launch_gemm_f32(P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
+          MUON_HIP(launch_gemm_f32(P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
+          MUON_HIP(launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(g.tiles_apply), g.n_tiles_apply, 1.f, a, first ? 0 : -1, s));
+        }
+      }
+    }
+    MUON_HIP(launch_apply_update(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->lr, (float)hp->weight_decay,
+                                 (float)hp->rms_scale, o_sel, use_s, ctx->ns_dtype, s));
+    if (update_rms_out) MUON_HIP(launch_update_rms(ctx->d_mats, ch.first, ch.count, use_s, update_rms_out, s));
+  }
+  ctx->last_o_sel = o_sel;
+  ctx->last_use_s = use_s;
+  ctx->last_chunk = (int)ctx->chunks.size() - 1;
+  return MUON_OK;
+}
+
+int muon_debug_read_update(muon_ctx* ctx, int32_t index, void* dst, int32_t dst_dtype, void* hip_stream) {
+  if (!ctx || !dst || index < 0 || index >= ctx->n) return MUON_E_INVALID_ARG;
+  if (dst_dtype != MUON_F32 && dst_dtype != MUON_BF16) return MUON_E_UNSUPPORTED_DTYPE;
+  if (ctx->last_chunk < 0 || ctx->mats[index].chunk != ctx->last_chunk) return MUON_E_NOT_RESIDENT;
+  MUON_HIP(launch_read_update(ctx->d_mats, index, ctx->last_o_sel, ctx->last_use_s, ctx->ns_dtype, dst, dst_dtype,
+                              static_cast<hipStream_t>(hip_stream)));
+  return MUON_OK;
+}
+
+int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t cap) {
+  if (!ctx || !out || index < 0 || index >= ctx->n || cap < 0) return MUON_E_INVALID_ARG;
+  const MatPlan& q = ctx->mats[index];
+  const int64_t v[8] = {q.m, q.n, q.transposed, q.mp, q.np, q.chunk, q.tile, q.tile};
+  const int k = std::min<int>(cap, 8);
+  for (int i = 0; i < k; ++i) out[i] = v[i];
+  return k;
+}
+
+int muon_plan_chunks(const muon_ctx* ctx) { return ctx ? (int)ctx->chunks.size() : MUON_E_INVALID_ARG; }
+
+void muon_destroy(muon_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->upload_done) {
+    (void)hipEventSynchronize(ctx->upload_done);
+    (void)hipEventDestroy(ctx->upload_done);
+  }
+  if (ctx->h_ptrs_pinned) (void)hipHostFree(ctx->h_ptrs_pinned);
+  delete ctx;
+}
+
+const char* muon_status_string(int status) {
+  switch (status) {
+    case MUON_OK: return "ok";
+    case MUON_E_INVALID_ARG: return "invalid argument";
+    case MUON_E_UNSUPPORTED_DTYPE: return "unsupported dtype";
+    case MUON_E_SHAPE_MISMATCH: return "parameter list does not match the one given at init";
+    case MUON_E_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MUON_E_HIP: return "HIP runtime error";
+    case MUON_E_NOT_RESIDENT: return "matrix temporaries are not resident";
+    case MUON_E_MISALIGNED: return "misaligned buffer";
+    default: return "unknown status";
+  }
+}
+
+int muon_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+// Host-callable launchers of the HIP kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "muon_tables.h"
+
+namespace muon {
+
+// GEMM tile shapes the bf16 MFMA kernel is instantiated for.
+enum GemmShape : int { kShape128 = 0, kShape256 = 1, kNumShapes = 2 };
+constexpr int kShapeTile[kNumShapes] = {128, 256};
+constexpr int kF32Tile = 64;   // block tile of the fp32 Newton-Schulz GEMM
+
+// One-time per-process kernel attribute setup (large dynamic LDS).  Returns a hipError_t.
+hipError_t gemm_setup();
+
+// a1-a3: momentum, sum of squares, cast + orient into both layouts.  One block per EwTile.
+hipError_t launch_momentum_norm_cast(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles,
+                                     float mu, int nesterov, int ns_dtype, hipStream_t s);
+
+// a2 second stage: fixed-order sum of the partials of each matrix, s = 1/(sqrt(sum)+eps).
+hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, double eps, hipStream_t s);
+
+// a4-a6: grouped NT GEMM with fused epilogue.  alpha_idx: -1 none, 0 -> scal[0], 1 -> scal[1].
+hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
+                            float beta_acc, float beta_e, int alpha_idx, hipStream_t s);
+hipError_t launch_gemm_f32(const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
+                           float beta_acc, float beta_e, int alpha_idx, hipStream_t s);
+
+// a8: W <- W - lr*(scale*O + wd*W); also leaves per-tile sums of O^2 in the partials.
+// o_sel: which buffer holds O in W's orientation for transposed matrices (Xt[o_sel]); use_s: multiply O by
+// scal[0] (only when no Newton-Schulz iteration ran).
+hipError_t launch_apply_update(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles,
+                               float lr, float wd, float rms_scale, int o_sel, int use_s, int ns_dtype,
+                               hipStream_t s);
+
+// sqrt(mean(O^2)) per matrix from the partials left by apply_update.
+hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int use_s, float* out, hipStream_t s);
+
+// Test hook: O of one matrix -> dst (rows x cols contiguous).
+hipError_t launch_read_update(const MatDesc* mats, int mat, int o_sel, int use_s, int ns_dtype, void* dst,
+                              int dst_dtype, hipStream_t s);
+
+}  // namespace muon

@@ -1,0 +1,62 @@
+// Device-visible tables shared by the host planner and the HIP kernels of the Muon step.
+// Plain-old-data only; every pointer is a device pointer into caller memory or the workspace.
+#pragma once
+#include <stdint.h>
+
+namespace muon {
+
+constexpr int kEwTile = 64;        // elementwise kernels work on 64x64 element tiles
+constexpr int kDtypeF32 = 0;
+constexpr int kDtypeBF16 = 1;
+
+// Static per-matrix record (built once at init).
+struct MatDesc {
+  void* X;            // m_pad x n_pad, row-major, NS dtype: the iterate in "rows <= cols" orientation
+  void* Xt[2];        // n_pad x m_pad: its transpose, ping-pong pair
+  void* Ag;           // m_pad x m_pad: Gram matrix X X^T
+  void* Bp;           // m_pad x m_pad: b*A + c*A*A
+  float* partials;    // one partial sum of squares per 64x64 tile
+  float* scal;        // [0] = 1/(||U||_F + eps), [1] = its square, [2] = sum(O^2) scratch, [3] spare
+  int32_t rows, cols; // A, B
+  int32_t m, n;       // min, max
+  int32_t mp, np;     // padded to the GEMM tile
+  int32_t transposed; // A > B: NS runs on U^T
+  int32_t w_dtype, g_dtype;
+  int32_t n_part;     // number of partials
+  int32_t ew_tiles_c; // 64-wide tile columns in U's orientation (padded)
+  float sqrt_max;     // sqrt(max(A, B))
+};
+
+// Per-step pointers (re-uploaded only when they change).
+struct MatPtrs {
+  void* w;
+  const void* g;
+  float* m;
+};
+
+// One 64x64 tile of an elementwise pass.
+struct EwTile {
+  int32_t mat;        // index into the chunk-local MatDesc / MatPtrs range (absolute matrix index)
+  int16_t tr, tc;     // tile row / column in U's (= W's) orientation
+};
+
+// One product  C[i][j] = sum_k L[i][k] * R[j][k]  ("NT": both operands contiguous along k),
+// followed by  val = alpha * (beta_acc * acc + beta_e * E[i][j])  and stores of C and/or its transpose.
+struct GemmProblem {
+  const void* L;      // M x K, leading dimension ldl
+  const void* R;      // N x K, leading dimension ldr
+  const void* E;      // M x N addend at the output position (may be null), leading dimension lde
+  void* C;            // M x N output (may be null), leading dimension ldc
+  void* Ct;           // N x M transposed output (may be null), leading dimension ldct
+  const float* scal;  // per-matrix scalars (alpha source)
+  int32_t K;
+  int32_t ldl, ldr, lde, ldc, ldct;
+  int32_t symmetric;  // output is symmetric: off-diagonal tiles are also stored mirrored into C
+};
+
+struct GemmTile {
+  int32_t prob;
+  int16_t ti, tj;     // tile row / column, in units of the kernel's block tile
+};
+
+}  // namespace muon

@@ -1,0 +1,124 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host-side
+logic (argument validation, workspace sizing, status strings) behaves without a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2502_16982_amd import binding as b
+    if not os.path.exists(b.library_path()):
+        from paper_2502_16982_amd import build
+        build.build_library()
+    return b
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "muon.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(muon_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree(binding):
+    assert declared_functions() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol(binding):
+    L = binding.lib()
+    for name in declared_functions():
+        assert hasattr(L, name), name
+
+
+def test_struct_layout_matches_header(binding):
+    assert C.sizeof(binding.muon_param) == 3 * 8 + 2 * 8 + 2 * 4
+    assert C.sizeof(binding.muon_hparams) == 8 * 8 + 2 * 4
+
+
+def test_default_hparams_are_the_papers(binding):
+    hp = binding.default_hparams()
+    assert (hp.a, hp.b, hp.c) == (3.4445, -4.7750, 2.0315)
+    assert hp.momentum == 0.95 and hp.ns_steps == 5 and hp.rms_scale == 0.2 and hp.nesterov == 1
+
+
+def test_status_strings(binding):
+    L = binding.lib()
+    seen = set()
+    for code in range(0, -8, -1):
+        s = L.muon_status_string(code).decode()
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert L.muon_status_string(-99).decode() == "unknown status"
+
+
+def test_workspace_bytes_validation(binding):
+    L = binding.lib()
+    out = C.c_size_t(0)
+    p = binding.param_array([(128, 256)], [0], [0])
+    assert L.muon_workspace_bytes(None, 1, 1, 0, C.byref(out)) == -1
+    assert L.muon_workspace_bytes(p, 0, 1, 0, C.byref(out)) == -1
+    assert L.muon_workspace_bytes(p, 1, 1, 0, None) == -1
+    assert L.muon_workspace_bytes(p, 1, 7, 0, C.byref(out)) == -2
+    bad = binding.param_array([(0, 256)], [0], [0])
+    assert L.muon_workspace_bytes(bad, 1, 1, 0, C.byref(out)) == -1
+    bad = binding.param_array([(8, 8)], [5], [0])
+    assert L.muon_workspace_bytes(bad, 1, 1, 0, C.byref(out)) == -2
+    huge = binding.param_array([(2 ** 21, 8)], [0], [0])
+    assert L.muon_workspace_bytes(huge, 1, 1, 0, C.byref(out)) == -1
+
+
+def test_workspace_bytes_scale_with_dtype_and_cap(binding):
+    shapes = [(1024, 1024)] * 4 + [(1024, 4096), (4096, 1024)]
+    p = binding.param_array(shapes, [1] * 6, [1] * 6)
+    bf = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16)
+    f32 = binding.muon_workspace_bytes(p, 6, binding.MUON_F32)
+    # temporaries: 3 m*n + 2 m*m elements per matrix
+    elems = sum(3 * a * b + 2 * min(a, b) ** 2 for a, b in shapes)
+    assert bf >= 2 * elems and bf < 2 * elems * 1.2 + (1 << 22)
+    assert f32 >= 4 * elems and f32 < 4 * elems * 1.2 + (1 << 22)
+    capped = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16, max_bytes=bf // 3)
+    assert capped < bf and capped % 256 == 0
+    tiny = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16, max_bytes=1)
+    one = 2 * (3 * 1024 * 4096 + 2 * 1024 * 1024)
+    assert one <= tiny < one + (1 << 22)
+
+
+def test_init_rejects_bad_arguments_before_touching_the_device(binding):
+    L = binding.lib()
+    ctx = C.c_void_p(None)
+    p = binding.param_array([(128, 256)], [0], [0])
+    assert L.muon_init(None, p, 1, 1, C.c_void_p(256), 1 << 30) == -1
+    assert L.muon_init(C.byref(ctx), p, 1, 1, None, 1 << 30) == -1
+    assert L.muon_init(C.byref(ctx), p, 1, 1, C.c_void_p(257), 1 << 30) == -7
+    assert L.muon_init(C.byref(ctx), p, 1, 1, C.c_void_p(256), 16) == -4
+    assert L.muon_init(C.byref(ctx), p, 1, 9, C.c_void_p(256), 1 << 30) == -2
+    assert ctx.value is None
+    assert L.muon_step(None, p, 1, C.byref(binding.default_hparams()), None, None) == -1
+    assert L.muon_plan_chunks(None) == -1
+    L.muon_destroy(None)  # no-op
+
+
+def test_missing_library_fails_loudly(binding, monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "library_path", lambda: str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        binding.lib()
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2502_16982_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"(from\s+oracle|import\s+oracle|oracle\.|oracle/|muon_oracle)", text), f
+    bench = open(os.path.join(ROOT, "bench.py")).read() if os.path.exists(os.path.join(ROOT, "bench.py")) else ""
+    # bench may use the oracle only for its cpu_baseline leg
+    for line in bench.splitlines():
+        if "oracle" in line and "import" in line:
+            assert "cpu_baseline" in bench

@@ -1,0 +1,70 @@
+"""GPU parity at the benchmark's full sizes: each workload is stepped whole, in the launch configuration
+the bench times, and sampled matrices (one per distinct shape) are checked against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2502_16982_amd import binding, workloads  # noqa: E402
+from tests import gpu_util as U  # noqa: E402
+from tests.test_gpu_parity import assert_records  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    binding.lib()
+    return torch.device("cuda:0")
+
+
+def first_of_each_shape(wl):
+    seen, idx = set(), []
+    for i, s in enumerate(wl.shapes):
+        if s not in seen:
+            seen.add(s)
+            idx.append(i)
+    return idx
+
+
+def test_dense12_w1024_full(dev):
+    wl = workloads.workload("dense12_w1024")
+    check = first_of_each_shape(wl) + [len(wl.shapes) - 1]
+    assert_records(U.run_and_compare(wl, dev, check=check), U.TOL_BF16_FRO)
+
+
+def test_moe_bank_full(dev):
+    wl = workloads.workload("moe_bank_66x2048x1408")
+    check = first_of_each_shape(wl) + [len(wl.shapes) - 1]
+    assert_records(U.run_and_compare(wl, dev, check=check), U.TOL_BF16_FRO)
+
+
+@pytest.mark.timeout(600)
+def test_block_w4096_full(dev):
+    wl = workloads.workload("block_w4096")
+    # 4096x4096 and 11008x4096 (transposed orientation) are checked elementwise against the oracle;
+    # the 4096x11008 matrices are covered by invariants below (their oracle run alone takes a minute)
+    assert_records(U.run_and_compare(wl, dev, check=[0, 6]), U.TOL_BF16_FRO)
+
+
+def test_block_w4096_invariants(dev):
+    """Properties that hold at any size: singular-value band of O, Lemma-1 update RMS, finite outputs."""
+    wl = workloads.workload("block_w4096")
+    tensors = workloads.make_all(wl, dev)
+    st = binding.MuonStepper(tensors)
+    hp, d = U.hp_from(wl.hyper)
+    rms = torch.zeros(len(tensors), device=dev)
+    st.step(hp, update_rms=rms)
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(wl.shapes):
+        o = st.read_update(i)
+        assert torch.isfinite(o).all()
+        r = float(rms[i]) * np.sqrt(max(a, b))
+        assert 0.68 * 0.98 <= r <= 1.21 * 1.02, (i, r)
+    # singular values of one rectangular O: bf16 NS keeps them inside a slightly widened band
+    o = st.read_update(4).double()
+    s = torch.linalg.svdvals(o.cpu())
+    assert s.max() <= 1.2024 * 1.03 and s.min() >= 0.0
+    assert (s > 0.68 * 0.97).double().mean() > 0.9
+    st.close()
