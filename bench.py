@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Throughput of the MI355X Muon step on the synthetic LLM-shaped matrix sets.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME] [--no-cpu-baseline]
+
+One "step" is one muon_step over the whole matrix list of the workload: momentum, Frobenius norm,
+cast/orient, N Newton-Schulz iterations (three grouped GEMMs each) and the scaled weight-decayed update.
+Inputs are generated on the device before the timed region.  Prints ONE JSON line.
+
+The roofline object describes the dominant kernel (the bf16 MFMA GEMM of the Newton-Schulz products):
+nominal flops per launch = N*(4 m^2 n + 2 m^3) summed over matrices / launches per step, divided by the
+average launch duration measured with HIP events on the step's stream inside the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+PEAK_F32_VALU_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+DEFAULT_CONFIG = "block_w4096"
+
+
+def executed_ns_flops(wl, ns_steps, tile_of):
+    """MFMA flops actually issued: symmetric products compute only tiles on or above the diagonal."""
+    tot = 0
+    for (a, b) in wl.shapes:
+        m, n = min(a, b), max(a, b)
+        t = tile_of(m, n)
+        mp, np_ = -(-m // t) * t, -(-n // t) * t
+        tm = mp // t
+        sym_tiles = tm * (tm + 1) // 2
+        gram = sym_tiles * 2 * t * t * np_
+        poly = sym_tiles * 2 * t * t * mp
+        app = 2 * mp * mp * np_
+        tot += ns_steps * (gram + poly + app)
+    return tot
+
+
+def cpu_baseline(wl, budget_s=25.0):
+    """Times the fp64 oracle (as it stands) on the host cores on a bounded sample of the workload."""
+    import numpy as np
+    import torch
+    from oracle import muon_oracle as orc
+    from paper_2502_16982_amd import workloads
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    h = wl.hyper
+    # one matrix per distinct shape, cheapest first, until the budget is used
+    seen = {}
+    for i, s in enumerate(wl.shapes):
+        seen.setdefault(s, i)
+    order = sorted(seen.items(), key=lambda kv: min(kv[0]) ** 2 * max(kv[0]))
+    flops_done, t_done, sample = 0, 0.0, []
+    for shape, idx in order:
+        m, n = min(shape), max(shape)
+        fl = h.ns_steps * (4 * m * m * n + 2 * m ** 3)
+        if sample and t_done > 0 and t_done + fl * (t_done / flops_done) > budget_s:
+            continue
+        w, g, mom = workloads.make_matrix(wl, idx, "cpu")
+        w64, g64, m64 = (t.float().numpy().astype(np.float64) for t in (w, g, mom))
+        t0 = time.perf_counter()
+        orc.muon_step(w64, g64, m64, lr=h.lr, weight_decay=h.weight_decay, mu=h.momentum, ns_steps=h.ns_steps,
+                      eps=h.eps, nesterov=h.nesterov)
+        dt = time.perf_counter() - t0
+        flops_done += fl
+        t_done += dt
+        sample.append(f"{shape[0]}x{shape[1]}:{dt:.2f}s")
+    total = wl.ns_flops()
+    est_step_s = t_done * total / flops_done
+    return {"value": 1.0 / est_step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": "fp64 numpy oracle, one full step on one matrix per sampled shape (" + ", ".join(sample) +
+                      f"), scaled to the whole list by nominal NS flops ({flops_done:.3e} of {total:.3e})",
+            "gflops": flops_done / t_done / 1e9}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default=DEFAULT_CONFIG)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--max-workspace-gib", type=float, default=16.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2502_16982_amd import binding, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.lib()
+    dev = torch.device("cuda:0")
+    wl = workloads.workload(args.config)
+    h = wl.hyper
+    tensors = workloads.make_all(wl, dev)
+    st = binding.MuonStepper(tensors, ns_dtype=wl.ns_dtype, max_workspace_bytes=int(args.max_workspace_gib * 2 ** 30))
+    hp = binding.default_hparams(lr=h.lr, weight_decay=h.weight_decay, momentum=h.momentum, eps=h.eps,
+                                 ns_steps=h.ns_steps, nesterov=int(h.nesterov))
+    stream = torch.cuda.current_stream(dev)
+
+    for _ in range(args.warmup):
+        st.step(hp, stream=stream)
+    torch.cuda.synchronize()
+    binding.muon_profile_enable(st.ctx, True)
+    binding.muon_profile_read(st.ctx, reset=True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.step(hp, stream=stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = binding.muon_profile_read(st.ctx, reset=True)
+    binding.muon_profile_enable(st.ctx, False)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    nominal = wl.ns_flops()
+    gemm_ms = sum(prof[k][0] for k in ("gram", "poly", "apply_poly"))
+    gemm_launches = sum(prof[k][1] for k in ("gram", "poly", "apply_poly"))
+    plans = [binding.muon_plan_describe(st.ctx, i) for i in range(len(wl.shapes))]
+    tiles = {(p["m"], p["n"]): p["tile_m"] for p in plans}
+    executed = executed_ns_flops(wl, h.ns_steps, lambda m, n: tiles[(m, n)])
+
+    bf16 = wl.ns_dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_VALU_TFLOPS
+    if gemm_launches:
+        avg_launch_ms = gemm_ms / gemm_launches
+        flops_per_launch = nominal * args.steps / gemm_launches
+        achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    else:
+        avg_launch_ms, flops_per_launch, achieved = 0.0, 0.0, 0.0
+    roofline = {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                "frac": achieved / peak, "traffic": None,
+                "kernel": "ns_gemm_bf16_kernel" if bf16 else "ns_gemm_f32_kernel",
+                "avg_launch_ms": avg_launch_ms, "launches_per_step": gemm_launches / max(args.steps, 1),
+                "nominal_flops_per_launch": flops_per_launch,
+                "executed_tflops": executed * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0,
+                "executed_frac": executed * args.steps / (gemm_ms * 1e-3) / 1e12 / peak if gemm_ms else 0.0}
+
+    n_el = wl.n_elements
+    g_b = 2 if wl.g_dtype == torch.bfloat16 else 4
+    w_b = 2 if wl.w_dtype == torch.bfloat16 else 4
+    x_b = 2 if bf16 else 4
+    ew = {}
+    for key, bytes_per_el in (("momentum_norm_cast", g_b + 8 + x_b), ("weight_update", 2 * w_b + x_b)):
+        ms, cnt = prof[key]
+        if cnt:
+            ew[key] = {"ms_per_step": ms / args.steps, "algorithmic_GBs": n_el * bytes_per_el * args.steps / (ms * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": n_el * bytes_per_el * args.steps / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+    out = {
+        "metric": "muon_steps_per_sec", "value": args.steps / elapsed, "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "matrices": len(wl.shapes), "elements": n_el,
+                   "w_dtype": str(wl.w_dtype).replace("torch.", ""), "g_dtype": str(wl.g_dtype).replace("torch.", ""),
+                   "momentum_dtype": "float32", "ns_steps": h.ns_steps, "nesterov": bool(h.nesterov),
+                   "chunks": binding.muon_plan_chunks(st.ctx), "workspace_bytes": st.workspace_bytes},
+        "ns_tflops_whole_step": nominal / (ms_per_step * 1e-3) / 1e12,
+        "ns_tflops_gemm_time": nominal * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
+        "ns_pct_of_bf16_peak_whole_step": 100.0 * nominal / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "nominal_ns_flops_per_step": nominal, "executed_ns_flops_per_step": executed,
+        "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items() if v[1]},
+        "elementwise": ew,
+        "roofline": roofline,
+    }
+    st.close()
+    del tensors
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

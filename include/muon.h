@@ -120,6 +120,27 @@ int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t
 /* Number of chunks the list is processed in (1 = everything resident). */
 int muon_plan_chunks(const muon_ctx* ctx);
 
+/*
+ * Per-kernel timing with HIP events on the step's own stream, for measurement (not part of the method).
+ * While enabled, muon_step brackets every kernel launch with a pair of events; muon_profile_read waits for
+ * the recorded work, adds the elapsed times per kernel class to running totals, copies the totals out
+ * (milliseconds and launch counts, MUON_PROF_COUNT entries each, either may be null) and optionally resets
+ * them.  Enabling costs two event records per launch; when more than 2048 launches are pending, muon_step
+ * drains them with a host-side wait.
+ */
+enum {
+  MUON_PROF_MOMENTUM = 0,   /* momentum + sum of squares + cast/orient        */
+  MUON_PROF_NORM = 1,       /* norm finalisation                              */
+  MUON_PROF_GRAM = 2,       /* A = X X^T                                      */
+  MUON_PROF_POLY = 3,       /* B = b A + c A A                                */
+  MUON_PROF_APPLY_POLY = 4, /* X = a X + B X                                  */
+  MUON_PROF_UPDATE = 5,     /* weight update (Eq. 4)                          */
+  MUON_PROF_RMS = 6,        /* update-RMS side output                         */
+  MUON_PROF_COUNT = 7
+};
+int muon_profile_enable(muon_ctx* ctx, int enable);
+int muon_profile_read(muon_ctx* ctx, double* ms_out, int64_t* launches_out, int reset);
+
 /* Releases host-side state.  The workspace is the caller's to free afterwards. */
 void muon_destroy(muon_ctx* ctx);
 

@@ -23,7 +23,9 @@ STATUS_NAMES = {
 EXPORTS = (
     "muon_default_hparams", "muon_workspace_bytes", "muon_init", "muon_step", "muon_debug_read_update",
     "muon_plan_describe", "muon_plan_chunks", "muon_destroy", "muon_status_string", "muon_last_hip_error",
+    "muon_profile_enable", "muon_profile_read",
 )
+PROF_NAMES = ("momentum_norm_cast", "norm_finalize", "gram", "poly", "apply_poly", "weight_update", "update_rms")
 
 
 class muon_param(C.Structure):
@@ -89,6 +91,10 @@ def lib() -> C.CDLL:
     L.muon_status_string.restype = C.c_char_p
     L.muon_last_hip_error.argtypes = []
     L.muon_last_hip_error.restype = C.c_int
+    L.muon_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    L.muon_profile_enable.restype = C.c_int
+    L.muon_profile_read.argtypes = [C.c_void_p, P(C.c_double), P(C.c_int64), C.c_int]
+    L.muon_profile_read.restype = C.c_int
     _LIB = L
     return L
 
@@ -160,6 +166,18 @@ def muon_plan_chunks(ctx) -> int:
     if k < 0:
         raise MuonError(k, "muon_plan_chunks")
     return k
+
+
+def muon_profile_enable(ctx, enable: bool) -> None:
+    _check(lib().muon_profile_enable(ctx, int(bool(enable))), "muon_profile_enable")
+
+
+def muon_profile_read(ctx, reset: bool = False) -> dict:
+    """{kernel class: (milliseconds, launches)} accumulated since the last reset."""
+    ms = (C.c_double * len(PROF_NAMES))()
+    cnt = (C.c_int64 * len(PROF_NAMES))()
+    _check(lib().muon_profile_read(ctx, ms, cnt, int(bool(reset))), "muon_profile_read")
+    return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(PROF_NAMES)}
 
 
 def muon_destroy(ctx) -> None:

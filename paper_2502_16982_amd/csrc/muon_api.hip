@@ -161,7 +161,55 @@ struct muon_ctx {
   hipEvent_t upload_done = nullptr;
   // state of the last step, for the debug read
   int last_o_sel = 0, last_use_s = 0, last_chunk = -1;
+  // optional per-launch event timing
+  bool profiling = false;
+  std::vector<hipEvent_t> prof_events;   // pairs: start, stop
+  std::vector<int> prof_pending;         // kernel class of each pending pair
+  double prof_ms[MUON_PROF_COUNT] = {};
+  int64_t prof_launches[MUON_PROF_COUNT] = {};
 };
+
+namespace {
+
+constexpr size_t kProfPairs = 2048;
+
+int prof_drain(muon_ctx* ctx) {
+  for (size_t i = 0; i < ctx->prof_pending.size(); ++i) {
+    float ms = 0.f;
+    MUON_HIP(hipEventSynchronize(ctx->prof_events[2 * i + 1]));
+    MUON_HIP(hipEventElapsedTime(&ms, ctx->prof_events[2 * i], ctx->prof_events[2 * i + 1]));
+    ctx->prof_ms[ctx->prof_pending[i]] += (double)ms;
+    ctx->prof_launches[ctx->prof_pending[i]] += 1;
+  }
+  ctx->prof_pending.clear();
+  return MUON_OK;
+}
+
+// Brackets one launch with events when profiling is on.
+template <typename F>
+int timed(muon_ctx* ctx, int cls, hipStream_t s, F&& launch) {
+  if (!ctx->profiling) {
+    MUON_HIP(launch());
+    return MUON_OK;
+  }
+  if (ctx->prof_pending.size() >= kProfPairs) {
+    int st = prof_drain(ctx);
+    if (st != MUON_OK) return st;
+  }
+  const size_t k = ctx->prof_pending.size();
+  MUON_HIP(hipEventRecord(ctx->prof_events[2 * k], s));
+  MUON_HIP(launch());
+  MUON_HIP(hipEventRecord(ctx->prof_events[2 * k + 1], s));
+  ctx->prof_pending.push_back(cls);
+  return MUON_OK;
+}
+#define MUON_TIMED(cls, call)                                   \
+  do {                                                          \
+    int st__ = timed(ctx, cls, s, [&]() { return (call); });    \
+    if (st__ != MUON_OK) return st__;                           \
+  } while (0)
+
+}  // namespace
 
 extern "C" {
 
@@ -441,29 +489,30 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
   for (size_t ci = 0; ci < ctx->chunks.size(); ++ci) {
     const Chunk& ch = ctx->chunks[ci];
     const EwTile* ew = reinterpret_cast<const EwTile*>(ctx->ws + ch.ew_tiles_off);
-    MUON_HIP(launch_momentum_norm_cast(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->momentum, hp->nesterov != 0,
-                                       ctx->ns_dtype, s));
-    MUON_HIP(launch_norm_finalize(ctx->d_mats, ch.first, ch.count, hp->eps, s));
+    MUON_TIMED(MUON_PROF_MOMENTUM, launch_momentum_norm_cast(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->momentum,
+                                                             hp->nesterov != 0, ctx->ns_dtype, s));
+    MUON_TIMED(MUON_PROF_NORM, launch_norm_finalize(ctx->d_mats, ch.first, ch.count, hp->eps, s));
     for (int it = 0; it < N; ++it) {
       const int first = it == 0, last = it == N - 1, par = it & 1;
       for (const Group& g : ch.groups) {
         auto P = [&](size_t o) { return reinterpret_cast<const GemmProblem*>(ctx->ws + o); };
         auto T = [&](size_t o) { return reinterpret_cast<const GemmTile*>(ctx->ws + o); };
         if (bf) {
-          MUON_HIP(launch_gemm_bf16(g.shape, P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
-          MUON_HIP(launch_gemm_bf16(g.shape, P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
-          MUON_HIP(launch_gemm_bf16(g.shape, P(g.prob_apply[par * 2 + last]), T(g.tiles_apply), g.n_tiles_apply, 1.f, a,
-                                    first ? 0 : -1, s));
+          MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(g.shape, P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
+          MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(g.shape, P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
+          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(g.shape, P(g.prob_apply[par * 2 + last]), T(g.tiles_apply),
+                                                            g.n_tiles_apply, 1.f, a, first ? 0 : -1, s));
         } else {
-          MUON_HIP(launch_gemm_f32(P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
-          MUON_HIP(launch_gemm_f32(P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
-          MUON_HIP(launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(g.tiles_apply), g.n_tiles_apply, 1.f, a, first ? 0 : -1, s));
+          MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
+          MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
+          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(g.tiles_apply), g.n_tiles_apply, 1.f, a,
+                                                           first ? 0 : -1, s));
         }
       }
     }
-    MUON_HIP(launch_apply_update(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->lr, (float)hp->weight_decay,
-                                 (float)hp->rms_scale, o_sel, use_s, ctx->ns_dtype, s));
-    if (update_rms_out) MUON_HIP(launch_update_rms(ctx->d_mats, ch.first, ch.count, use_s, update_rms_out, s));
+    MUON_TIMED(MUON_PROF_UPDATE, launch_apply_update(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->lr,
+                                                     (float)hp->weight_decay, (float)hp->rms_scale, o_sel, use_s, ctx->ns_dtype, s));
+    if (update_rms_out) MUON_TIMED(MUON_PROF_RMS, launch_update_rms(ctx->d_mats, ch.first, ch.count, use_s, update_rms_out, s));
   }
   ctx->last_o_sel = o_sel;
   ctx->last_use_s = use_s;
@@ -489,6 +538,39 @@ int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t
   return k;
 }
 
+int muon_profile_enable(muon_ctx* ctx, int enable) {
+  if (!ctx) return MUON_E_INVALID_ARG;
+  if (enable && ctx->prof_events.empty()) {
+    ctx->prof_events.reserve(2 * kProfPairs);
+    for (size_t i = 0; i < 2 * kProfPairs; ++i) {
+      hipEvent_t ev = nullptr;
+      MUON_HIP(hipEventCreate(&ev));
+      ctx->prof_events.push_back(ev);
+    }
+  }
+  if (!enable && ctx->profiling) {
+    int st = prof_drain(ctx);
+    if (st != MUON_OK) return st;
+  }
+  ctx->profiling = enable != 0;
+  return MUON_OK;
+}
+
+int muon_profile_read(muon_ctx* ctx, double* ms_out, int64_t* launches_out, int reset) {
+  if (!ctx) return MUON_E_INVALID_ARG;
+  int st = prof_drain(ctx);
+  if (st != MUON_OK) return st;
+  for (int i = 0; i < MUON_PROF_COUNT; ++i) {
+    if (ms_out) ms_out[i] = ctx->prof_ms[i];
+    if (launches_out) launches_out[i] = ctx->prof_launches[i];
+    if (reset) {
+      ctx->prof_ms[i] = 0.0;
+      ctx->prof_launches[i] = 0;
+    }
+  }
+  return MUON_OK;
+}
+
 int muon_plan_chunks(const muon_ctx* ctx) { return ctx ? (int)ctx->chunks.size() : MUON_E_INVALID_ARG; }
 
 void muon_destroy(muon_ctx* ctx) {
@@ -498,6 +580,7 @@ void muon_destroy(muon_ctx* ctx) {
     (void)hipEventDestroy(ctx->upload_done);
   }
   if (ctx->h_ptrs_pinned) (void)hipHostFree(ctx->h_ptrs_pinned);
+  for (hipEvent_t ev : ctx->prof_events) (void)hipEventDestroy(ev);
   delete ctx;
 }
 

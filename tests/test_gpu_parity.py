@@ -88,7 +88,9 @@ def test_bf16_outliers(dev):
 def test_ns_step_counts(dev, ns_steps):
     wl = workloads.custom("steps", [(192, 320), (320, 192)], seed_base=25)
     recs = U.run_and_compare(wl, dev, hp_over={"ns_steps": ns_steps})
-    assert_records(recs, U.TOL_BF16_FRO if ns_steps else 5e-3)
+    # the quintic is expansive around its fixed point (|f'(0.868)| = 1.58), so bf16 rounding noise grows with
+    # the iteration count: the 2e-2 bound is stated for N <= 5; N = 10 gets 5e-2
+    assert_records(recs, {0: 5e-3, 10: 5e-2}.get(ns_steps, U.TOL_BF16_FRO))
     wl32 = workloads.custom("steps32", [(96, 160), (160, 96)], w_dtype=torch.float32, g_dtype=torch.float32, ns_dtype="f32",
                             w_std=1.0, g_std=1.0, seed_base=26)
     assert_records(U.run_and_compare(wl32, dev, hp_over={"ns_steps": ns_steps}), U.TOL_F32_FRO)
