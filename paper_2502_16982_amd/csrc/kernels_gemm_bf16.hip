@@ -1,0 +1,405 @@
+// bf16 Newton-Schulz products for gfx950 (Eq. 2 of the paper): grouped "NT" GEMMs
+//     C[i][j] = sum_k L[i][k] * R[j][k]          (bf16 operands, fp32 accumulation on the matrix cores)
+// with a fused epilogue  val = alpha * (beta_acc * acc + beta_e * E[i][j]).  All three products of one
+// iteration have this form once the iterate is kept in both layouts (X and X^T):
+//     Gram       A  = X X^T            L = R = X        (symmetric output)
+//     polynomial B  = b A + c A A      L = R = A        (A symmetric, so A A = A A^T; symmetric output)
+//     apply      X' = a X + B X        L = B, R = X^T   (stores X' and/or X'^T)
+// Operands are zero-padded to whole tiles by the producer, so the kernel has no edge handling.
+//
+// Design for CDNA4:
+//  * v_mfma_f32_32x32x16_bf16 (the 16x16x32 form runs at half the rate on this chip), wave tile = FM x FN
+//    MFMA tiles, accumulators stay in registers for the whole K loop.
+//  * K is consumed in 64-wide slabs, i.e. one 128-byte line per row: measured on this chip, the L1 hands a
+//    compute unit ~57 B/clk when 8 lanes ask for a whole line and only ~26 B/clk for half lines.
+//    Global memory -> LDS goes through the LDS-DMA path (global_load_lds_dwordx4): no staging registers, no
+//    ds_write instructions.  A wave-level DMA instruction fills 1 KB of LDS contiguously (lane i -> byte 16*i),
+//    i.e. 8 rows of 128 B; the 16-byte chunks of a row are XOR-swizzled by (row/2)%8 - each lane simply fetches
+//    the global chunk that belongs in its slot - so that the 16 lanes served together by a ds_read_b128
+//    fragment read hit 16 distinct bank groups (the bank-conflict counter reads zero).
+//  * The LDS stages form a ring; a slab is requested one whole iteration (64 MFMAs per wave for the 256x256
+//    tile) before it is needed.  One s_waitcnt + s_barrier per slab, placed in front of the last k-step so
+//    that the next slab's first fragments are already being read while that k-step's MFMAs execute.
+//  * Epilogue: the (transposed) addend tile is DMA-ed into LDS with coalesced 16-byte requests, each lane
+//    combines it with its accumulators (fp32 math, one v_cvt_pk_bf16_f32 rounding), and results leave through
+//    swizzled LDS images so that both the tile and its transpose are written with full 16-byte-per-lane
+//    coalesced stores; the second orientation comes from a 2-MFMA transpose per 32x32 tile.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "muon_launch.h"
+
+namespace muon {
+namespace {
+
+typedef unsigned short u16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef const __attribute__((address_space(1))) void* gptr;
+typedef __attribute__((address_space(3))) void* lptr;
+
+constexpr int BK = 64;        // K slab in elements: one 128-byte line per row, the request size the L1 serves at full rate
+constexpr int ROWB = 128;     // bytes per LDS row of a pipeline stage (BK bf16, unpadded, swizzled)
+
+__device__ __forceinline__ float bf16_to_f32(u16 h) { return __uint_as_float(((unsigned)h) << 16); }
+__device__ __forceinline__ u16 f32_to_bf16(float f) {
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u16)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (u16)(u >> 16);
+}
+
+// s_waitcnt vmcnt(N), other counters untouched (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <int BM, int BN>
+struct TileCfg {
+  static constexpr size_t pipeline_bytes(int nstage) { return (size_t)nstage * (BM + BN) * ROWB; }
+  static constexpr size_t image_bytes() { return (size_t)BM * BN * 2; }
+  static constexpr size_t lds_main(int nstage) {
+    return pipeline_bytes(nstage) > image_bytes() ? pipeline_bytes(nstage) : image_bytes();
+  }
+  static constexpr size_t lds_bytes(int nstage) { return lds_main(nstage); }
+};
+
+// s_waitcnt vmcnt(N) lgkmcnt(0): used in front of the barrier, where this wave's LDS reads must have returned too
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_lgkm0() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
+}
+
+#ifdef MUON_DBG_TIMING
+__device__ long long g_dbg_t[64 * 8];
+__device__ long long g_dbg_blk[8192 * 4];
+__device__ long long g_dbg_clk[8192 * 2];
+#define DBG_BLK(slot) do { if (tid == 0 && blockIdx.x < 8192) g_dbg_blk[blockIdx.x * 4 + (slot)] = (slot) == 3 ? (long long)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)) | ((long long)__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11)) << 32) : (long long)wall_clock64(); } while (0)
+#define DBG_T(slot) do { if (blockIdx.x == 300 && tid == 0 && kt >= 8 && kt < 16) g_dbg_t[(kt - 8) * 8 + (slot)] = clock64(); } while (0)
+#else
+#define DBG_T(slot) do {} while (0)
+#define DBG_BLK(slot) do {} while (0)
+#endif
+
+template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB>
+__global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const GemmProblem* __restrict__ probs,
+                                                                            const GemmTile* __restrict__ tiles,
+                                                                            float beta_acc, float beta_e, int alpha_idx) {
+  constexpr int NW = WM_ * WN_, NT = NW * 64;
+  constexpr int WTM = BM / WM_, WTN = BN / WN_;    // wave tile
+  constexpr int FM = WTM / 32, FN = WTN / 32;      // 32x32 MFMA tiles per wave
+  constexpr int LI = BM / 8 / NW, RI = BN / 8 / NW;     // DMA instructions per wave per slab (8 rows each)
+  constexpr int NLOAD = LI + RI;
+  constexpr int STAGE_B = (BM + BN) * ROWB;        // bytes per stage
+  constexpr int KSTEPS = BK / 16;                  // MFMA k-steps per slab
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+  static_assert(NW % 2 == 0 && NSTAGE == 2 && NLOAD < 32 && FM % 2 == 0, "pipeline shape");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const GemmTile tile = tiles[blockIdx.x];
+  const GemmProblem p = probs[tile.prob];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN_, wn = wave % WN_;
+  const int row0 = tile.ti * BM, col0 = tile.tj * BN;
+
+  // ---- DMA addressing: a wave instruction fills 8 rows x 128 B; lane i -> slot (row i/8, chunk position i%8).
+  // Position s of row R holds logical chunk s ^ ((R/2)%8); R = 8*(instruction index) + i/8 and the instruction
+  // index has the parity of the wave number.
+  const int dma_row = wave * 8 + (lane >> 3);
+  const int dma_key = ((lane >> 4) & 3) + 4 * (wave & 1);
+  const int dma_chunk = (lane & 7) ^ dma_key;
+  const u16* lsrc = static_cast<const u16*>(p.L) + (size_t)(row0 + dma_row) * p.ldl + dma_chunk * 8;
+  const u16* rsrc = static_cast<const u16*>(p.R) + (size_t)(col0 + dma_row) * p.ldr + dma_chunk * 8;
+  const size_t lstep = (size_t)(8 * NW) * p.ldl, rstep = (size_t)(8 * NW) * p.ldr;
+  auto request = [&](int kt, int stage) {
+    unsigned char* base = smem + stage * STAGE_B + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < LI; ++i)
+      __builtin_amdgcn_global_load_lds((gptr)(lsrc + i * lstep + (size_t)kt * BK), (lptr)(base + i * NW * 1024), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < RI; ++i)
+      __builtin_amdgcn_global_load_lds((gptr)(rsrc + i * rstep + (size_t)kt * BK),
+                                       (lptr)(base + BM * ROWB + i * NW * 1024), 16, 0, 0);
+  };
+
+  // ---- fragment addressing: lane (r = lane%32, h = lane/32) reads logical chunk 2*kk + h of its row ----
+  const int fr = lane & 31, fh = lane >> 5;
+  const int fkey = (fr >> 1) & 7;
+  const int a_base = (wm * WTM + fr) * ROWB, b_base = BM * ROWB + (wn * WTN + fr) * ROWB;
+
+  f32x16 acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  bf16x8 af[KSTEPS][FM], bfr[KSTEPS][FN];
+  auto fread = [&](int stage, int kk) {
+    const unsigned char* s = smem + stage * STAGE_B + (((2 * kk + fh) ^ fkey) * 16);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(s + a_base + i * 32 * ROWB);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(s + b_base + j * 32 * ROWB);
+  };
+  auto mma = [&](int kk) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[i][j], 0, 0, 0);
+  };
+  // ---- pipeline: two LDS stages.  A wave instruction that requests 1 KB keeps the wave's (in-order) issue port
+  // busy until the memory pipeline accepts it - measured ~57 clocks each when 4 waves request 16 KB apiece in a
+  // burst - so requests are never issued in a burst: one request follows every second MFMA.  The loop is skewed
+  // by one k-step so that no MFMA ever waits for LDS latency.  Iteration kt (slab kt sits in stage `cur`):
+  //   A  MFMAs of k-step 3 of slab kt-1, interleaved with the fragment reads of k-steps 0..2 of slab kt
+  //   B  fragment reads of k-step 3, MFMAs of k-step 0; then barrier #1: nobody reads stage `cur` any more
+  //   C  MFMAs of k-steps 1 and 2, interleaved with the requests of slab kt+2 into stage `cur`
+  //      then wait until slab kt+1 (requested one iteration ago) has landed, barrier #2.
+  const int KT = p.K / BK;
+  DBG_BLK(0);
+#ifdef MUON_DBG_TIMING
+  if (tid == 0 && blockIdx.x < 8192) g_dbg_clk[blockIdx.x * 2] = clock64();
+#endif
+  request(0, 0);
+  if (KT > 1) { request(1, 1); wait_vmcnt<NLOAD>(); } else { wait_vmcnt<0>(); }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) af[KSTEPS - 1][i][t] = (__bf16)0.0f;     // first pass of phase A multiplies zeros
+#pragma unroll
+  for (int j = 0; j < FN; ++j)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) bfr[KSTEPS - 1][j][t] = (__bf16)0.0f;
+
+  int cur = 0;
+  int kt = 0;
+  // one iteration; REFILL: slab kt+2 exists and is requested; SYNC: slab kt+1 exists and must be visible afterwards
+  auto iteration = [&](auto refill_tag, auto sync_tag) {
+    constexpr bool REFILL = decltype(refill_tag)::value, SYNC = decltype(sync_tag)::value;
+    DBG_T(0);
+    // A
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS - 1; ++kk) fread(cur, kk);
+    mma(KSTEPS - 1);
+#pragma unroll
+    for (int g = 0; g < (KSTEPS - 1) * (FM + FN) / 3; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN * 3) / ((KSTEPS - 1) * (FM + FN)), 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    DBG_T(1);
+    // B
+    fread(cur, KSTEPS - 1);
+    mma(0);
+    __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    DBG_T(2);
+    if (REFILL) {
+      wait_vmcnt_lgkm0<NLOAD>();                 // my fragment reads have returned (slab kt+1's requests may be in flight)
+      __builtin_amdgcn_s_barrier();              // barrier #1: stage `cur` is free
+      DBG_T(3);
+      request(kt + 2, cur);
+    }
+    // C
+#pragma unroll
+    for (int kk = 1; kk < KSTEPS - 1; ++kk) mma(kk);
+    if (REFILL) {
+#pragma unroll
+      for (int g = 0; g < NLOAD; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, ((KSTEPS - 2) * FM * FN) / NLOAD, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    DBG_T(4);
+    if (SYNC) {
+      if (REFILL) wait_vmcnt<NLOAD>(); else wait_vmcnt<0>();   // slab kt+1 has landed (slab kt+2 may be in flight)
+      __builtin_amdgcn_s_barrier();              // barrier #2: ... for every wave
+    }
+    DBG_T(5);
+    cur ^= 1;
+    ++kt;
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  while (kt + 2 < KT) iteration(T_{}, T_{});
+  if (kt + 1 < KT) iteration(F_{}, T_{});
+  iteration(F_{}, F_{});
+  mma(KSTEPS - 1);                               // k-step 3 of the last slab
+  DBG_BLK(1);
+#ifdef MUON_DBG_TIMING
+  if (tid == 0 && blockIdx.x < 8192) g_dbg_clk[blockIdx.x * 2 + 1] = clock64();
+#endif
+
+  // ======================================= epilogue =======================================
+  // val = alpha * (beta_acc*acc + beta_e*E).  Each lane owns, per MFMA tile, one column c and rows 8q+4h+e
+  // (e = 0..3 contiguous): exactly 8 contiguous bytes of the TRANSPOSED tile.  So the transposed addend tile is
+  // DMA-ed into an LDS image [BN][BM] (16-byte chunks of row c XOR-swizzled by c%16), each lane replaces its
+  // 8-byte pieces in place with the results, and the image leaves with coalesced 16-byte stores: that is Ct.
+  // For C the packed results are transposed on the matrix cores (P^T = P^T * I with a 0/1 selector operand,
+  // exact in fp32), which hands each lane 8 contiguous bytes of a ROW of the tile; same image trick, [BM][BN].
+  wait_vmcnt<0>();
+  __syncthreads();                               // every wave is done with the pipeline stages
+  const float alpha = alpha_idx >= 0 ? p.scal[alpha_idx] : 1.f;
+  const u16* Et = static_cast<const u16*>(p.Et);
+  u16* C = static_cast<u16*>(p.C);
+  u16* Ct = static_cast<u16*>(p.Ct);
+  int ldct = p.ldct;
+  if (p.symmetric) {                             // mirror store below the diagonal; T itself only off the diagonal
+    Ct = C;
+    ldct = p.ldc;
+    if (tile.ti == tile.tj) C = nullptr;
+  }
+  constexpr int CPT = BM / 8;                    // 16-byte chunks per row of the transposed image
+  constexpr int RPI_T = 64 / CPT;                // image rows per wave-level DMA instruction / per 64 lanes
+  constexpr int TI = BN / RPI_T / NW;            // DMA instructions (or 64-lane store groups) per wave
+
+  if (Et) {
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+      const int c = (i * NW + wave) * RPI_T + lane / CPT;
+      const int chunk = (lane % CPT) ^ (c & 15);
+      __builtin_amdgcn_global_load_lds((gptr)(Et + (size_t)(col0 + c) * p.ldet + row0 + chunk * 8),
+                                       (lptr)(smem + (i * NW + wave) * 1024), 16, 0, 0);
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+  }
+
+  u32x2 pk[FM][FN][4];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int c = wn * WTN + j * 32 + fr;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int lchunk = (wm * WTM + i * 32) / 8 + q;
+        unsigned char* slot = smem + c * (BM * 2) + ((lchunk ^ (c & 15)) * 16) + fh * 8;
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = beta_acc * acc[i][j][4 * q + e];
+        if (Et) {
+          const u32x2 ev = *reinterpret_cast<const u32x2*>(slot);
+          x[0] = fmaf(beta_e, __uint_as_float(ev.x << 16), x[0]);
+          x[1] = fmaf(beta_e, __uint_as_float(ev.x & 0xffff0000u), x[1]);
+          x[2] = fmaf(beta_e, __uint_as_float(ev.y << 16), x[2]);
+          x[3] = fmaf(beta_e, __uint_as_float(ev.y & 0xffff0000u), x[3]);
+        }
+        const f32x2 lo = {alpha * x[0], alpha * x[1]}, hi = {alpha * x[2], alpha * x[3]};
+        pk[i][j][q].x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
+        pk[i][j][q].y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2));
+        if (Ct) *reinterpret_cast<u32x2*>(slot) = pk[i][j][q];   // this slot belongs to this lane alone
+      }
+    }
+
+  if (Ct) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+      const int c = (i * NW + wave) * RPI_T + lane / CPT;
+      const int chunk = (lane % CPT) ^ (c & 15);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + (i * NW + wave) * 1024 + lane * 16);
+      *reinterpret_cast<u32x4*>(Ct + (size_t)(col0 + c) * ldct + row0 + chunk * 8) = v;
+    }
+  }
+  if (C) {
+    // selector operand: k index (h, t) of k-step s stands for tile row 16s + 4h + t (t < 4) or 16s + 8 + 4h + t - 4
+    bf16x8 sel[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int row = 16 * s + 4 * fh + (t < 4 ? t : 4 + t);
+        sel[s][t] = (__bf16)(fr == row ? 1.0f : 0.0f);
+      }
+    constexpr int CPR = BN / 8;                  // 16-byte chunks per row of the row-major image
+    constexpr int RPI_C = 64 / CPR;
+    constexpr int CI = BM / RPI_C / NW;
+    __syncthreads();                             // the transposed image has been read out (or the addend consumed)
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        f32x16 d;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) d[v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+          const u32x4 raw = {pk[i][j][2 * s].x, pk[i][j][2 * s].y, pk[i][j][2 * s + 1].x, pk[i][j][2 * s + 1].y};
+          d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), sel[s], d, 0, 0, 0);
+        }
+        const int r = wm * WTM + i * 32 + fr;    // this lane now holds row r, columns 8q + 4h + e of the MFMA tile
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int lchunk = (wn * WTN + j * 32) / 8 + q;
+          const f32x2 lo = {d[4 * q], d[4 * q + 1]}, hi = {d[4 * q + 2], d[4 * q + 3]};
+          u32x2 w;
+          w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
+          w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2));
+          *reinterpret_cast<u32x2*>(smem + r * (BN * 2) + ((lchunk ^ (r & 15)) * 16) + fh * 8) = w;
+        }
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < CI; ++i) {
+      const int r = (i * NW + wave) * RPI_C + lane / CPR;
+      const int chunk = (lane % CPR) ^ (r & 15);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + (i * NW + wave) * 1024 + lane * 16);
+      *reinterpret_cast<u32x4*>(C + (size_t)(row0 + r) * p.ldc + col0 + chunk * 8) = v;
+    }
+  }
+  DBG_BLK(2);
+  DBG_BLK(3);
+}
+
+// ---- instantiations: {tile, waves, stages, waves per SIMD} per GemmShape ----
+#define GEMM_S128 ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2>
+#ifdef MUON_GEMM_256_W8
+#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 4, 2, 2>
+#define GEMM_S256_THREADS 512
+#else
+#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1>
+#define GEMM_S256_THREADS 256
+#endif
+constexpr size_t kLds128 = TileCfg<128, 128>::lds_bytes(2);
+constexpr size_t kLds256 = TileCfg<256, 256>::lds_bytes(2);
+
+}  // namespace
+
+hipError_t gemm_setup() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&GEMM_S128), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)kLds128);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&GEMM_S256), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)kLds256);
+}
+
+hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
+                            float beta_e, int alpha_idx, hipStream_t s) {
+  if (n_tiles <= 0) return hipSuccess;
+  if (shape == kShape128)
+    GEMM_S128<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx);
+  else if (shape == kShape256)
+    GEMM_S256<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace muon

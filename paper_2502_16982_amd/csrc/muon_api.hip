@@ -52,8 +52,8 @@ struct MatPlan {
 struct Group {
   int shape;
   int n_prob;
-  size_t prob_gram, prob_poly, prob_apply[4];  // byte offsets of the problem tables in the table region
-  size_t tiles_sym, tiles_apply;               // byte offsets of the tile tables
+  size_t prob_gram, prob_poly, prob_apply[4];  // byte offsets of the problem tables ([parity * 2 + last])
+  size_t tiles_sym, tiles_apply, tiles_apply_last;   // byte offsets of the tile tables
   int n_tiles_sym, n_tiles_apply;
 };
 
@@ -69,6 +69,47 @@ struct Chunk {
 int pick_shape(int m, int n) {
   if (m % 256 == 0 && n % 256 == 0 && m >= 1024) return kShape256;
   return kShape128;
+}
+
+// The bf16 kernel's cheap output is the transposed one: a last iteration that needs only X is posed swapped.
+bool swapped_last(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16 && !q.transposed; }
+
+// Workgroups are handed to the 8 accelerator dies (XCDs, each with a private L2) round-robin by workgroup index:
+// entry b of a tile table runs on XCD b % 8.  Tiles that share operand panels are therefore dealt to the same
+// XCD: when a launch holds many problems, each goes whole to the least-loaded XCD; otherwise every problem is
+// cut into 8 contiguous runs of its row-major tile list.  Problems arrive longest-first, so the tail of a launch
+// is made of short tiles.
+constexpr int kXcds = 8;
+void deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTile* out) {
+  std::vector<std::vector<GemmTile>> seq(kXcds);
+  int rr = 0;
+  const bool whole = per_problem.size() >= 4 * (size_t)kXcds;
+  for (const std::vector<GemmTile>& tiles : per_problem) {
+    if (whole) {
+      // least-loaded XCD, ties broken round-robin
+      int best = rr;
+      for (int x = 0; x < kXcds; ++x)
+        if (seq[(rr + x) % kXcds].size() < seq[best].size()) best = (rr + x) % kXcds;
+      seq[best].insert(seq[best].end(), tiles.begin(), tiles.end());
+      rr = (rr + 1) % kXcds;
+    } else {
+      const size_t n = tiles.size();
+      for (int x = 0; x < kXcds; ++x) {
+        const size_t lo = n * x / kXcds, hi = n * (x + 1) / kXcds;
+        seq[x].insert(seq[x].end(), tiles.begin() + lo, tiles.begin() + hi);
+      }
+    }
+  }
+  size_t o = 0;
+  for (size_t s = 0;; ++s) {
+    bool any = false;
+    for (int x = 0; x < kXcds; ++x)
+      if (s < seq[x].size()) {
+        out[o++] = seq[x][s];
+        any = true;
+      }
+    if (!any) break;
+  }
 }
 
 int validate_shapes(const muon_param* p, int32_t n, int32_t ns_dtype) {
@@ -122,7 +163,7 @@ struct TableLayout {
 size_t gemm_tables_bytes_for(const MatPlan& q) {
   const int tm = q.mp / q.tile, tn = q.np / q.tile;
   const size_t sym = (size_t)tm * (tm + 1) / 2, app = (size_t)tm * tn;
-  return 6 * sizeof(GemmProblem) + (sym + app) * sizeof(GemmTile);
+  return 6 * sizeof(GemmProblem) + (sym + 2 * app) * sizeof(GemmTile);
 }
 
 TableLayout table_layout(const std::vector<MatPlan>& mp, size_t total_partials) {
@@ -379,21 +420,30 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         GemmProblem gp{};
         gp.scal = d.scal;
         // Gram: A = X X^T
-        gp.L = d.X; gp.R = d.X; gp.E = nullptr; gp.C = d.Ag; gp.Ct = nullptr;
-        gp.K = q.np; gp.ldl = q.np; gp.ldr = q.np; gp.lde = 0; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+        gp.L = d.X; gp.R = d.X; gp.E = nullptr; gp.Et = nullptr; gp.C = d.Ag; gp.Ct = nullptr;
+        gp.K = q.np; gp.ldl = q.np; gp.ldr = q.np; gp.lde = 0; gp.ldet = 0; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
         reinterpret_cast<GemmProblem*>(img.data() + g.prob_gram)[k] = gp;
-        // polynomial: B = b A + c A A
-        gp.L = d.Ag; gp.R = d.Ag; gp.E = d.Ag; gp.C = d.Bp; gp.Ct = nullptr;
-        gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.mp; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+        // polynomial: B = b A + c A A  (A is symmetric, so it is its own transposed addend)
+        gp.L = d.Ag; gp.R = d.Ag; gp.E = d.Ag; gp.Et = d.Ag; gp.C = d.Bp; gp.Ct = nullptr;
+        gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.mp; gp.ldet = q.mp; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
         reinterpret_cast<GemmProblem*>(img.data() + g.prob_poly)[k] = gp;
-        // apply: X' = a X + B X, reading X^T from Xt[p], writing X in place and X'^T to Xt[p^1];
-        // the last iteration writes only the layout W needs
+        // apply: X' = a X + B X, reading X^T from Xt[p], writing X in place and X'^T to Xt[p^1].
+        // The last iteration writes only the layout W needs; when that is X itself, the bf16 kernel gets the
+        // product posed the other way round (X'^T = X^T B, output through its transposed store).
         for (int par = 0; par < 2; ++par)
           for (int last = 0; last < 2; ++last) {
-            gp.L = d.Bp; gp.R = d.Xt[par]; gp.E = d.X; gp.C = d.X; gp.Ct = d.Xt[par ^ 1];
-            gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.np; gp.ldc = q.np; gp.ldct = q.mp; gp.symmetric = 0;
+            gp.L = d.Bp; gp.R = d.Xt[par]; gp.E = d.X; gp.Et = d.Xt[par]; gp.C = d.X; gp.Ct = d.Xt[par ^ 1];
+            gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.np; gp.ldet = q.mp; gp.ldc = q.np; gp.ldct = q.mp;
+            gp.symmetric = 0;
             if (last) {
-              if (q.transposed) gp.C = nullptr; else gp.Ct = nullptr;
+              if (q.transposed) {
+                gp.C = nullptr;
+              } else if (swapped_last(q, ns_dtype)) {
+                gp.L = d.Xt[par]; gp.R = d.Bp; gp.E = nullptr; gp.Et = d.X; gp.C = nullptr; gp.Ct = d.X;
+                gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = 0; gp.ldet = q.np; gp.ldc = 0; gp.ldct = q.np;
+              } else {
+                gp.Ct = nullptr;
+              }
             }
             reinterpret_cast<GemmProblem*>(img.data() + g.prob_apply[par * 2 + last])[k] = gp;
           }
@@ -408,16 +458,26 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
       }
       g.tiles_sym = take(n_sym * sizeof(GemmTile));
       g.tiles_apply = take(n_app * sizeof(GemmTile));
-      GemmTile* ts = reinterpret_cast<GemmTile*>(img.data() + g.tiles_sym);
-      GemmTile* ta = reinterpret_cast<GemmTile*>(img.data() + g.tiles_apply);
-      size_t is = 0, ia = 0;
-      for (size_t k = 0; k < members.size(); ++k) {
-        const MatPlan& q = ctx->mats[members[k]];
-        const int tm = q.mp / q.tile, tn = q.np / q.tile;
-        for (int i = 0; i < tm; ++i)
-          for (int j = i; j < tm; ++j) ts[is++] = GemmTile{(int32_t)k, (int16_t)i, (int16_t)j};
-        for (int i = 0; i < tm; ++i)
-          for (int j = 0; j < tn; ++j) ta[ia++] = GemmTile{(int32_t)k, (int16_t)i, (int16_t)j};
+      g.tiles_apply_last = take(n_app * sizeof(GemmTile));
+      {
+        std::vector<std::vector<GemmTile>> sym(members.size()), app(members.size()), app_last(members.size());
+        for (size_t k = 0; k < members.size(); ++k) {
+          const MatPlan& q = ctx->mats[members[k]];
+          const int tm = q.mp / q.tile, tn = q.np / q.tile;
+          for (int i = 0; i < tm; ++i)
+            for (int j = i; j < tm; ++j) sym[k].push_back(GemmTile{(int32_t)k, (int16_t)i, (int16_t)j});
+          for (int i = 0; i < tm; ++i)
+            for (int j = 0; j < tn; ++j) app[k].push_back(GemmTile{(int32_t)k, (int16_t)i, (int16_t)j});
+          if (swapped_last(q, ns_dtype)) {
+            for (int i = 0; i < tn; ++i)
+              for (int j = 0; j < tm; ++j) app_last[k].push_back(GemmTile{(int32_t)k, (int16_t)i, (int16_t)j});
+          } else {
+            app_last[k] = app[k];
+          }
+        }
+        deal_tiles(sym, reinterpret_cast<GemmTile*>(img.data() + g.tiles_sym));
+        deal_tiles(app, reinterpret_cast<GemmTile*>(img.data() + g.tiles_apply));
+        deal_tiles(app_last, reinterpret_cast<GemmTile*>(img.data() + g.tiles_apply_last));
       }
       g.n_tiles_sym = (int)n_sym;
       g.n_tiles_apply = (int)n_app;
@@ -500,12 +560,14 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
         if (bf) {
           MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(g.shape, P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
           MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(g.shape, P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
-          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(g.shape, P(g.prob_apply[par * 2 + last]), T(g.tiles_apply),
-                                                            g.n_tiles_apply, 1.f, a, first ? 0 : -1, s));
+          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(g.shape, P(g.prob_apply[par * 2 + last]),
+                                                            T(last ? g.tiles_apply_last : g.tiles_apply), g.n_tiles_apply, 1.f, a,
+                                                            first ? 0 : -1, s));
         } else {
           MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
           MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
-          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(g.tiles_apply), g.n_tiles_apply, 1.f, a,
+          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]),
+                                                           T(last ? g.tiles_apply_last : g.tiles_apply), g.n_tiles_apply, 1.f, a,
                                                            first ? 0 : -1, s));
         }
       }

@@ -42,15 +42,18 @@ struct EwTile {
 
 // One product  C[i][j] = sum_k L[i][k] * R[j][k]  ("NT": both operands contiguous along k),
 // followed by  val = alpha * (beta_acc * acc + beta_e * E[i][j])  and stores of C and/or its transpose.
+// The bf16 kernel writes Ct straight from the accumulator layout and C through one extra MFMA transpose,
+// so single-output problems are posed with Ct as the output.
 struct GemmProblem {
   const void* L;      // M x K, leading dimension ldl
   const void* R;      // N x K, leading dimension ldr
   const void* E;      // M x N addend at the output position (may be null), leading dimension lde
+  const void* Et;     // the same addend stored transposed, N x M, leading dimension ldet (bf16 kernel reads this one)
   void* C;            // M x N output (may be null), leading dimension ldc
   void* Ct;           // N x M transposed output (may be null), leading dimension ldct
   const float* scal;  // per-matrix scalars (alpha source)
   int32_t K;
-  int32_t ldl, ldr, lde, ldc, ldct;
+  int32_t ldl, ldr, lde, ldet, ldc, ldct;
   int32_t symmetric;  // output is symmetric: off-diagonal tiles are also stored mirrored into C
 };
 
