@@ -21,8 +21,13 @@ __device__ __forceinline__ u16 f32_to_bf16(float f) {
   return (u16)(u >> 16);
 }
 
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round-to-nearest-even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ unsigned pack2(float lo, float hi) {
-  return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Deterministic block-wide sum (256 threads): butterfly inside each wave, then the 4 wave sums in order.
@@ -170,10 +175,13 @@ __global__ __launch_bounds__(256) void momentum_norm_cast_kernel(const MatDesc* 
   const EwTile t = tiles[blockIdx.x];
   const MatDesc d = mats[t.mat];
   const MatPtrs pt = ptrs[t.mat];
-  if (d.g_dtype == kDtypeBF16)
-    momentum_tile<u16, XT>(d, pt, t.tr, t.tc, mu, nesterov, lds, red);
-  else
-    momentum_tile<float, XT>(d, pt, t.tr, t.tc, mu, nesterov, lds, red);
+  for (int k = 0; k < t.count; ++k) {
+    if (k) __syncthreads();     // the LDS tile and the reduction scratch are reused
+    if (d.g_dtype == kDtypeBF16)
+      momentum_tile<u16, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, lds, red);
+    else
+      momentum_tile<float, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, lds, red);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -251,10 +259,13 @@ __global__ __launch_bounds__(256) void apply_update_kernel(const MatDesc* __rest
   const MatPtrs pt = ptrs[t.mat];
   float scale = rms_scale * d.sqrt_max;
   if (use_s) scale *= d.scal[0];
-  if (d.w_dtype == kDtypeBF16)
-    apply_tile<u16, XT>(d, pt, t.tr, t.tc, lr, wd, scale, o_sel, red);
-  else
-    apply_tile<float, XT>(d, pt, t.tr, t.tc, lr, wd, scale, o_sel, red);
+  for (int k = 0; k < t.count; ++k) {
+    if (k) __syncthreads();     // the reduction scratch is reused
+    if (d.w_dtype == kDtypeBF16)
+      apply_tile<u16, XT>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
+    else
+      apply_tile<float, XT>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
+  }
 }
 
 // sqrt(mean(O^2)) per matrix from the per-tile sums left by apply_update_kernel.

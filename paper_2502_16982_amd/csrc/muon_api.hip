@@ -380,10 +380,12 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
       for (int i = ch.first; i < ch.first + ch.count; ++i) {
         const MatPlan& q = ctx->mats[i];
         for (int r = 0; r < q.ew_tr; ++r)
-          for (int c = 0; c < q.ew_tc; ++c) {
+          for (int c = 0; c < q.ew_tc; c += kEwRun) {
             t[ch.n_ew_tiles].mat = i;
             t[ch.n_ew_tiles].tr = (int16_t)r;
             t[ch.n_ew_tiles].tc = (int16_t)c;
+            t[ch.n_ew_tiles].count = (int16_t)std::min(kEwRun, q.ew_tc - c);
+            t[ch.n_ew_tiles].pad_ = 0;
             ch.n_ew_tiles++;
           }
       }

@@ -34,10 +34,13 @@ struct MatPtrs {
   float* m;
 };
 
-// One 64x64 tile of an elementwise pass.
+// One work item of an elementwise pass: `count` consecutive 64x64 tiles of one tile row.
+constexpr int kEwRun = 4;          // tiles per work item (amortises the table look-ups of a block)
 struct EwTile {
-  int32_t mat;        // index into the chunk-local MatDesc / MatPtrs range (absolute matrix index)
-  int16_t tr, tc;     // tile row / column in U's (= W's) orientation
+  int32_t mat;        // absolute matrix index (into MatDesc / MatPtrs)
+  int16_t tr, tc;     // tile row / first tile column in U's (= W's) orientation
+  int16_t count;      // 1 .. kEwRun
+  int16_t pad_;
 };
 
 // One product  C[i][j] = sum_k L[i][k] * R[j][k]  ("NT": both operands contiguous along k),
