@@ -80,6 +80,19 @@ bool swapped_last(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16
 // cut into 8 contiguous runs of its row-major tile list.  Problems arrive longest-first, so the tail of a launch
 // is made of short tiles.
 constexpr int kXcds = 8;
+
+// Tiles of one problem in an order whose consecutive runs of 32 (one tile per compute unit of an XCD) form
+// 4 x 8 blocks of the tile grid: the 32 tiles running together on an XCD then share 4 row panels and 8 column
+// panels, which they sweep along k in step, instead of 1 + 32 panels for a row-major run.
+void blocked_tiles(int32_t prob, int tm, int tn, bool upper_only, std::vector<GemmTile>& out) {
+  constexpr int BH = 4, BW = 8;
+  for (int bi = 0; bi < tm; bi += BH)
+    for (int bj = 0; bj < tn; bj += BW)
+      for (int i = bi; i < std::min(bi + BH, tm); ++i)
+        for (int j = bj; j < std::min(bj + BW, tn); ++j)
+          if (!upper_only || j >= i) out.push_back(GemmTile{prob, (int16_t)i, (int16_t)j});
+}
+
 void deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTile* out) {
   std::vector<std::vector<GemmTile>> seq(kXcds);
   int rr = 0;
@@ -466,16 +479,12 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         for (size_t k = 0; k < members.size(); ++k) {
           const MatPlan& q = ctx->mats[members[k]];
           const int tm = q.mp / q.tile, tn = q.np / q.tile;
-          for (int i = 0; i < tm; ++i)
-            for (int j = i; j < tm; ++j) sym[k].push_back(GemmTile{(int32_t)k, (int16_t)i, (int16_t)j});
-          for (int i = 0; i < tm; ++i)
-            for (int j = 0; j < tn; ++j) app[k].push_back(GemmTile{(int32_t)k, (int16_t)i, (int16_t)j});
-          if (swapped_last(q, ns_dtype)) {
-            for (int i = 0; i < tn; ++i)
-              for (int j = 0; j < tm; ++j) app_last[k].push_back(GemmTile{(int32_t)k, (int16_t)i, (int16_t)j});
-          } else {
+          blocked_tiles((int32_t)k, tm, tm, true, sym[k]);
+          blocked_tiles((int32_t)k, tm, tn, false, app[k]);
+          if (swapped_last(q, ns_dtype))
+            blocked_tiles((int32_t)k, tn, tm, false, app_last[k]);
+          else
             app_last[k] = app[k];
-          }
         }
         deal_tiles(sym, reinterpret_cast<GemmTile*>(img.data() + g.tiles_sym));
         deal_tiles(app, reinterpret_cast<GemmTile*>(img.data() + g.tiles_apply));
