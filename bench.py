@@ -29,19 +29,25 @@ PEAK_HBM_GBS = 8000.0
 DEFAULT_CONFIG = "block_w4096"
 
 
-def executed_ns_flops(wl, ns_steps, tile_of):
-    """MFMA flops actually issued: symmetric products compute only tiles on or above the diagonal."""
+def executed_ns_flops(wl, ns_steps, fine, coarse):
+    """MFMA flops actually issued: symmetric products compute only tiles on or above the diagonal; the part of
+    an output that whole `coarse` tiles cover uses them, the remaining strips use `fine` tiles."""
+    def tiles(tm, tn, upper, skip_m=0, skip_n=0):
+        return sum(1 for i in range(tm) for j in range(tn) if (not upper or j >= i) and not (i < skip_m and j < skip_n))
     tot = 0
+    cache = {}
     for (a, b) in wl.shapes:
         m, n = min(a, b), max(a, b)
-        t = tile_of(m, n)
-        mp, np_ = -(-m // t) * t, -(-n // t) * t
-        tm = mp // t
-        sym_tiles = tm * (tm + 1) // 2
-        gram = sym_tiles * 2 * t * t * np_
-        poly = sym_tiles * 2 * t * t * mp
-        app = 2 * mp * mp * np_
-        tot += ns_steps * (gram + poly + app)
+        if (m, n) not in cache:
+            mp, np_ = -(-m // fine) * fine, -(-n // fine) * fine
+            cm, cn = (mp // coarse, np_ // coarse) if coarse else (0, 0)
+            r = coarse // fine if coarse else 1
+            sym_c, app_c = tiles(cm, cm, True), tiles(cm, cn, False)
+            sym_f = tiles(mp // fine, mp // fine, True, cm * r, cm * r)
+            app_f = tiles(mp // fine, np_ // fine, False, cm * r, cn * r)
+            area = lambda c, f: c * coarse * coarse + f * fine * fine
+            cache[(m, n)] = 2 * (area(sym_c, sym_f) * np_ + area(sym_c, sym_f) * mp + area(app_c, app_f) * mp)
+        tot += ns_steps * cache[(m, n)]
     return tot
 
 
@@ -131,9 +137,7 @@ def main() -> int:
     nominal = wl.ns_flops()
     gemm_ms = sum(prof[k][0] for k in ("gram", "poly", "apply_poly"))
     gemm_launches = sum(prof[k][1] for k in ("gram", "poly", "apply_poly"))
-    plans = [binding.muon_plan_describe(st.ctx, i) for i in range(len(wl.shapes))]
-    tiles = {(p["m"], p["n"]): p["tile_m"] for p in plans}
-    executed = executed_ns_flops(wl, h.ns_steps, lambda m, n: tiles[(m, n)])
+    executed = executed_ns_flops(wl, h.ns_steps, 128 if wl.ns_dtype == "bf16" else 64, 256 if wl.ns_dtype == "bf16" else 0)
 
     bf16 = wl.ns_dtype == "bf16"
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_VALU_TFLOPS

@@ -82,11 +82,13 @@ __device__ __forceinline__ void wait_vmcnt_lgkm0() {
 __device__ long long g_dbg_t[64 * 8];
 __device__ long long g_dbg_blk[8192 * 4];
 __device__ long long g_dbg_clk[8192 * 2];
+#define DBG_E(slot) do { if (blockIdx.x == 300 && tid == 0) g_dbg_t[400 + (slot)] = clock64(); } while (0)
 #define DBG_BLK(slot) do { if (tid == 0 && blockIdx.x < 8192) g_dbg_blk[blockIdx.x * 4 + (slot)] = (slot) == 3 ? (long long)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)) | ((long long)__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11)) << 32) : (long long)wall_clock64(); } while (0)
 #define DBG_T(slot) do { if (blockIdx.x == 300 && tid == 0 && kt >= 8 && kt < 16) g_dbg_t[(kt - 8) * 8 + (slot)] = clock64(); } while (0)
 #else
 #define DBG_T(slot) do {} while (0)
 #define DBG_BLK(slot) do {} while (0)
+#define DBG_E(slot) do {} while (0)
 #endif
 
 template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB>
@@ -102,6 +104,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   constexpr int KSTEPS = BK / 16;                  // MFMA k-steps per slab
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
   static_assert(NW % 2 == 0 && NSTAGE == 2 && NLOAD < 32 && FM % 2 == 0, "pipeline shape");
+  static_assert(4 * FM == WTM / 8 && (WTM / 8 & (WTM / 8 - 1)) == 0 && BM / 8 >= 16, "slot addressing: 4i+q and wm*WTM/8 use disjoint bits");
 
   extern __shared__ __align__(16) unsigned char smem[];
 
@@ -185,6 +188,28 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
     for (int t = 0; t < 8; ++t) bfr[KSTEPS - 1][j][t] = (__bf16)0.0f;
 
+  // Transposed addend tile -> LDS image [BN][BM]; wave-level DMA instruction idx fills image bytes [1024 idx, +1024).
+  // The half of the image that lies in the stage the last iteration no longer needs is requested during that
+  // iteration (`early`), the rest after the main loop.
+  const u16* Et = static_cast<const u16*>(p.Et);
+  constexpr int CPT = BM / 8;                    // 16-byte chunks per row of the transposed image
+  constexpr int RPI_T = 64 / CPT;                // image rows per wave-level DMA instruction / per 64 lanes
+  constexpr int TI = BN / RPI_T / NW;            // DMA instructions (or 64-lane store groups) per wave
+  constexpr int IPS = STAGE_B / 1024 / NW;       // image DMA instructions per wave that land in one pipeline stage
+  auto et_request = [&](int region) {            // requests the part of the image that overlays pipeline stage `region`
+    if (region * IPS >= TI) return;
+    const int idx0 = region * IPS * NW + wave;
+    const int c0 = idx0 * RPI_T + lane / CPT;
+    const u16* src = Et + (size_t)(col0 + c0) * p.ldet + row0;
+    unsigned char* dstl = smem + idx0 * 1024;
+#pragma unroll
+    for (int i = 0; i < (IPS < TI ? IPS : TI); ++i) {
+      const int c = c0 + i * NW * RPI_T;
+      const int chunk = (lane % CPT) ^ (c & (CPT - 1));
+      __builtin_amdgcn_global_load_lds((gptr)(src + (size_t)(i * NW * RPI_T) * p.ldet + chunk * 8), (lptr)(dstl + i * NW * 1024), 16, 0, 0);
+    }
+  };
+
   int cur = 0;
   int kt = 0;
   // one iteration; REFILL: slab kt+2 exists and is requested; SYNC: slab kt+1 exists and must be visible afterwards
@@ -216,8 +241,16 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       request(kt + 2, cur);
     }
     // C
+    if (!REFILL && !SYNC && Et) et_request(cur ^ 1);
 #pragma unroll
     for (int kk = 1; kk < KSTEPS - 1; ++kk) mma(kk);
+    if (!REFILL && !SYNC) {
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, ((KSTEPS - 2) * FM * FN) / 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+      }
+    }
     if (REFILL) {
 #pragma unroll
       for (int g = 0; g < NLOAD; ++g) {
@@ -249,14 +282,16 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   // ======================================= epilogue =======================================
   // val = alpha * (beta_acc*acc + beta_e*E).  Each lane owns, per MFMA tile, one column c and rows 8q+4h+e
   // (e = 0..3 contiguous): exactly 8 contiguous bytes of the TRANSPOSED tile.  So the transposed addend tile is
-  // DMA-ed into an LDS image [BN][BM] (16-byte chunks of row c XOR-swizzled by c%16), each lane replaces its
+  // DMA-ed into an LDS image [BN][BM] (16-byte chunks of row c XOR-swizzled by c % chunks-per-row), each lane replaces its
   // 8-byte pieces in place with the results, and the image leaves with coalesced 16-byte stores: that is Ct.
   // For C the packed results are transposed on the matrix cores (P^T = P^T * I with a 0/1 selector operand,
   // exact in fp32), which hands each lane 8 contiguous bytes of a ROW of the tile; same image trick, [BM][BN].
+  DBG_E(0);
   wait_vmcnt<0>();
   __syncthreads();                               // every wave is done with the pipeline stages
+  DBG_E(1);
   const float alpha = alpha_idx >= 0 ? p.scal[alpha_idx] : 1.f;
-  const u16* Et = static_cast<const u16*>(p.Et);
+  const float ab_acc = alpha * beta_acc, ab_e = alpha * beta_e;   // val = alpha*(beta_acc*acc + beta_e*E), alpha folded in
   u16* C = static_cast<u16*>(p.C);
   u16* Ct = static_cast<u16*>(p.Ct);
   int ldct = p.ldct;
@@ -265,59 +300,88 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     ldct = p.ldc;
     if (tile.ti == tile.tj) C = nullptr;
   }
-  constexpr int CPT = BM / 8;                    // 16-byte chunks per row of the transposed image
-  constexpr int RPI_T = 64 / CPT;                // image rows per wave-level DMA instruction / per 64 lanes
-  constexpr int TI = BN / RPI_T / NW;            // DMA instructions (or 64-lane store groups) per wave
-
   if (Et) {
-#pragma unroll
-    for (int i = 0; i < TI; ++i) {
-      const int c = (i * NW + wave) * RPI_T + lane / CPT;
-      const int chunk = (lane % CPT) ^ (c & 15);
-      __builtin_amdgcn_global_load_lds((gptr)(Et + (size_t)(col0 + c) * p.ldet + row0 + chunk * 8),
-                                       (lptr)(smem + (i * NW + wave) * 1024), 16, 0, 0);
-    }
+    et_request(cur ^ 1);        // `cur` was flipped after the last iteration: cur^1 is the stage that iteration still read
+    DBG_E(2);
     wait_vmcnt<0>();
     __syncthreads();
   }
+  DBG_E(3);
 
+  // Each lane's slot for (MFMA tile i, j; quarter q): image row c = wn*WTN + 32j + r, logical chunk
+  // wm*WTM/8 + 4i + q, half h.  The swizzle key c % CPT equals r % CPT, so the slot address is a per-lane base
+  // XOR a compile-time constant.  The addend pieces of tile t+1 are read while tile t is being combined.
   u32x2 pk[FM][FN][4];
+  const unsigned slot_base = (unsigned)((wn * WTN + fr) * (BM * 2) + fh * 8) + ((unsigned)((wm * (WTM / 8)) ^ (fr & (CPT - 1))) << 4);
+  auto slot_of = [&](int i, int j, int q) -> unsigned char* {
+    return smem + ((slot_base + (unsigned)(j * 32 * BM * 2)) ^ (unsigned)((4 * i + q) << 4));
+  };
+  auto combine = [&](auto has_e) {
+    constexpr bool HAS_E = decltype(has_e)::value;
+    u32x2 ev[2][4];
+    if (HAS_E) {
 #pragma unroll
-  for (int i = 0; i < FM; ++i)
+      for (int q = 0; q < 4; ++q) ev[0][q] = *reinterpret_cast<const u32x2*>(slot_of(0, 0, q));
+    }
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int c = wn * WTN + j * 32 + fr;
+    for (int t = 0; t < FM * FN; ++t) {
+      const int i = t / FN, j = t % FN;
+      if (HAS_E && t + 1 < FM * FN) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          ev[(t + 1) & 1][q] = *reinterpret_cast<const u32x2*>(slot_of((t + 1) / FN, (t + 1) % FN, q));
+      }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int lchunk = (wm * WTM + i * 32) / 8 + q;
-        unsigned char* slot = smem + c * (BM * 2) + ((lchunk ^ (c & 15)) * 16) + fh * 8;
         float x[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = beta_acc * acc[i][j][4 * q + e];
-        if (Et) {
-          const u32x2 ev = *reinterpret_cast<const u32x2*>(slot);
-          x[0] = fmaf(beta_e, __uint_as_float(ev.x << 16), x[0]);
-          x[1] = fmaf(beta_e, __uint_as_float(ev.x & 0xffff0000u), x[1]);
-          x[2] = fmaf(beta_e, __uint_as_float(ev.y << 16), x[2]);
-          x[3] = fmaf(beta_e, __uint_as_float(ev.y & 0xffff0000u), x[3]);
+        for (int e = 0; e < 4; ++e) x[e] = ab_acc * acc[i][j][4 * q + e];
+        if (HAS_E) {
+          const u32x2 e2 = ev[t & 1][q];
+          x[0] = fmaf(ab_e, __uint_as_float(e2.x << 16), x[0]);
+          x[1] = fmaf(ab_e, __uint_as_float(e2.x & 0xffff0000u), x[1]);
+          x[2] = fmaf(ab_e, __uint_as_float(e2.y << 16), x[2]);
+          x[3] = fmaf(ab_e, __uint_as_float(e2.y & 0xffff0000u), x[3]);
         }
-        const f32x2 lo = {alpha * x[0], alpha * x[1]}, hi = {alpha * x[2], alpha * x[3]};
+        const f32x2 lo = {x[0], x[1]}, hi = {x[2], x[3]};
         pk[i][j][q].x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
         pk[i][j][q].y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2));
-        if (Ct) *reinterpret_cast<u32x2*>(slot) = pk[i][j][q];   // this slot belongs to this lane alone
+        *reinterpret_cast<u32x2*>(slot_of(i, j, q)) = pk[i][j][q];   // this slot belongs to this lane alone
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  if (Et) combine(std::true_type{}); else combine(std::false_type{});
 
-  if (Ct) {
+  DBG_E(4);
+  {
     __syncthreads();
+    DBG_E(5);
+    constexpr int SB = TI < 8 ? TI : 8;          // image chunks read per batch before they are stored
+    // image row of step i: c = c_first + i * (NW * RPI_T); the swizzle key c % 16 only has period 16 / (NW * RPI_T)
+    constexpr int CSTEP = NW * RPI_T, PERIOD = CPT / CSTEP > 0 ? CPT / CSTEP : 1;
+    const int c_first = wave * RPI_T + lane / CPT;
+    u16* dst[PERIOD];
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
-      const int c = (i * NW + wave) * RPI_T + lane / CPT;
-      const int chunk = (lane % CPT) ^ (c & 15);
-      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + (i * NW + wave) * 1024 + lane * 16);
-      *reinterpret_cast<u32x4*>(Ct + (size_t)(col0 + c) * ldct + row0 + chunk * 8) = v;
+    for (int k = 0; k < PERIOD; ++k) {
+      const int c = c_first + k * CSTEP;
+      dst[k] = Ct + (size_t)(col0 + c) * ldct + row0 + ((lane % CPT) ^ (c & (CPT - 1))) * 8;
+    }
+    const size_t dstep = (size_t)(CSTEP * PERIOD) * ldct;
+#pragma unroll
+    for (int i0 = 0; i0 < TI; i0 += SB) {
+      u32x4 v[SB];
+#pragma unroll
+      for (int u = 0; u < SB; ++u) v[u] = *reinterpret_cast<const u32x4*>(smem + ((i0 + u) * NW + wave) * 1024 + lane * 16);
+#pragma unroll
+      for (int u = 0; u < SB; ++u) {
+        const int i = i0 + u;
+        *reinterpret_cast<u32x4*>(dst[i % PERIOD] + (size_t)(i / PERIOD) * dstep) = v[u];
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
+  DBG_E(6);
   if (C) {
     // selector operand: k index (h, t) of k-step s stands for tile row 16s + 4h + t (t < 4) or 16s + 8 + 4h + t - 4
     bf16x8 sel[2];
@@ -352,18 +416,36 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
           u32x2 w;
           w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
           w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2));
-          *reinterpret_cast<u32x2*>(smem + r * (BN * 2) + ((lchunk ^ (r & 15)) * 16) + fh * 8) = w;
+          *reinterpret_cast<u32x2*>(smem + r * (BN * 2) + ((lchunk ^ (r & (CPR - 1))) * 16) + fh * 8) = w;
         }
       }
+    DBG_E(7);
     __syncthreads();
+    DBG_E(8);
+    constexpr int SB = CI < 8 ? CI : 8;
+    constexpr int RSTEP = NW * RPI_C, PERIOD = CPR / RSTEP > 0 ? CPR / RSTEP : 1;
+    const int r_first = wave * RPI_C + lane / CPR;
+    u16* dst[PERIOD];
 #pragma unroll
-    for (int i = 0; i < CI; ++i) {
-      const int r = (i * NW + wave) * RPI_C + lane / CPR;
-      const int chunk = (lane % CPR) ^ (r & 15);
-      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + (i * NW + wave) * 1024 + lane * 16);
-      *reinterpret_cast<u32x4*>(C + (size_t)(row0 + r) * p.ldc + col0 + chunk * 8) = v;
+    for (int k = 0; k < PERIOD; ++k) {
+      const int r = r_first + k * RSTEP;
+      dst[k] = C + (size_t)(row0 + r) * p.ldc + col0 + ((lane % CPR) ^ (r & (CPR - 1))) * 8;
+    }
+    const size_t dstep = (size_t)(RSTEP * PERIOD) * p.ldc;
+#pragma unroll
+    for (int i0 = 0; i0 < CI; i0 += SB) {
+      u32x4 v[SB];
+#pragma unroll
+      for (int u = 0; u < SB; ++u) v[u] = *reinterpret_cast<const u32x4*>(smem + ((i0 + u) * NW + wave) * 1024 + lane * 16);
+#pragma unroll
+      for (int u = 0; u < SB; ++u) {
+        const int i = i0 + u;
+        *reinterpret_cast<u32x4*>(dst[i % PERIOD] + (size_t)(i / PERIOD) * dstep) = v[u];
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
+  DBG_E(9);
   DBG_BLK(2);
   DBG_BLK(3);
 }

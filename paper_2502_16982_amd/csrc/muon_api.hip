@@ -40,21 +40,26 @@ struct MatPlan {
   int64_t rows, cols;
   int m, n, mp, np, transposed;
   int w_dtype, g_dtype;
-  int shape;        // GemmShape (bf16) or 0 (fp32)
-  int tile;         // GEMM block tile in elements
+  int tile;         // fine GEMM block tile = padding granule, in elements
   int chunk;
   int ew_tr, ew_tc; // 64x64 tiles in U's orientation (padded)
   size_t ns_bytes;  // X + 2 Xt + Ag + Bp
   size_t part_off;  // first partial (floats)
 };
 
-// Launch group: the matrices of one chunk that share a GEMM block tile.
+// Tile tables of one block-tile size (byte offsets in the table region).
+struct TileSet {
+  size_t sym = 0, apply = 0, apply_last = 0;
+  int n_sym = 0, n_apply = 0, n_apply_last = 0;
+};
+
+// Launch group: all matrices of one chunk.  Each product is one launch per block-tile size: the 256x256 kernel
+// covers the part of every output that whole 256-tiles can cover, the fine kernel (128x128 bf16, 64x64 fp32)
+// the remaining strips, so that nothing is padded beyond the fine tile.
 struct Group {
-  int shape;
   int n_prob;
   size_t prob_gram, prob_poly, prob_apply[4];  // byte offsets of the problem tables ([parity * 2 + last])
-  size_t tiles_sym, tiles_apply, tiles_apply_last;   // byte offsets of the tile tables
-  int n_tiles_sym, n_tiles_apply;
+  TileSet fine, coarse;
 };
 
 struct Chunk {
@@ -64,12 +69,7 @@ struct Chunk {
   std::vector<Group> groups;
 };
 
-// GEMM block tile for a matrix.  256x256 tiles halve the LDS traffic per flop but need dimensions that are
-// whole multiples of 256 to avoid padding waste, and enough tiles to fill 256 compute units.
-int pick_shape(int m, int n) {
-  if (m % 256 == 0 && n % 256 == 0 && m >= 1024) return kShape256;
-  return kShape128;
-}
+constexpr int kCoarse = 256;   // block tile of the large bf16 kernel
 
 // The bf16 kernel's cheap output is the transposed one: a last iteration that needs only X is posed swapped.
 bool swapped_last(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16 && !q.transposed; }
@@ -84,16 +84,17 @@ constexpr int kXcds = 8;
 // Tiles of one problem in an order whose consecutive runs of 32 (one tile per compute unit of an XCD) form
 // 4 x 8 blocks of the tile grid: the 32 tiles running together on an XCD then share 4 row panels and 8 column
 // panels, which they sweep along k in step, instead of 1 + 32 panels for a row-major run.
-void blocked_tiles(int32_t prob, int tm, int tn, bool upper_only, std::vector<GemmTile>& out) {
+// Tiles (i, j) with i < skip_m and j < skip_n are left out (they are covered by the coarser kernel).
+void blocked_tiles(int32_t prob, int tm, int tn, bool upper_only, int skip_m, int skip_n, std::vector<GemmTile>& out) {
   constexpr int BH = 4, BW = 8;
   for (int bi = 0; bi < tm; bi += BH)
     for (int bj = 0; bj < tn; bj += BW)
       for (int i = bi; i < std::min(bi + BH, tm); ++i)
         for (int j = bj; j < std::min(bj + BW, tn); ++j)
-          if (!upper_only || j >= i) out.push_back(GemmTile{prob, (int16_t)i, (int16_t)j});
+          if ((!upper_only || j >= i) && !(i < skip_m && j < skip_n)) out.push_back(GemmTile{prob, (int16_t)i, (int16_t)j});
 }
 
-void deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTile* out) {
+size_t deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTile* out) {
   std::vector<std::vector<GemmTile>> seq(kXcds);
   int rr = 0;
   const bool whole = per_problem.size() >= 4 * (size_t)kXcds;
@@ -123,6 +124,7 @@ void deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTile*
       }
     if (!any) break;
   }
+  return o;
 }
 
 int validate_shapes(const muon_param* p, int32_t n, int32_t ns_dtype) {
@@ -149,13 +151,7 @@ void plan_matrices(const muon_param* p, int n, int ns_dtype, std::vector<MatPlan
     q.n = (int)std::max(q.rows, q.cols);
     q.w_dtype = p[i].w_dtype;
     q.g_dtype = p[i].g_dtype;
-    if (ns_dtype == MUON_BF16) {
-      q.shape = pick_shape(q.m, q.n);
-      q.tile = kShapeTile[q.shape];
-    } else {
-      q.shape = 0;
-      q.tile = kF32Tile;
-    }
+    q.tile = ns_dtype == MUON_BF16 ? kShapeTile[kShape128] : kF32Tile;
     q.mp = round_up_i(q.m, q.tile);
     q.np = round_up_i(q.n, q.tile);
     const int ap = q.transposed ? q.np : q.mp, bp = q.transposed ? q.mp : q.np;
@@ -405,20 +401,16 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
       cursor += (size_t)ch.n_ew_tiles * sizeof(EwTile);
     }
 
-    // GEMM groups of the chunk
-    const int n_shapes = ns_dtype == MUON_BF16 ? (int)kNumShapes : 1;
-    for (int s = 0; s < n_shapes; ++s) {
+    // GEMM group of the chunk
+    {
       std::vector<int> members;
-      for (int i = ch.first; i < ch.first + ch.count; ++i)
-        if (ctx->mats[i].shape == s) members.push_back(i);
-      if (members.empty()) continue;
+      for (int i = ch.first; i < ch.first + ch.count; ++i) members.push_back(i);
       // longest work first, so that the tail of the launch is made of short tiles
       std::stable_sort(members.begin(), members.end(), [&](int x, int y) {
         const MatPlan &a = ctx->mats[x], &b = ctx->mats[y];
         return (int64_t)a.np + a.mp > (int64_t)b.np + b.mp;
       });
       Group g{};
-      g.shape = s;
       g.n_prob = (int)members.size();
       auto take = [&](size_t bytes) {
         cursor = align_up(cursor, 256);
@@ -463,35 +455,38 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
             reinterpret_cast<GemmProblem*>(img.data() + g.prob_apply[par * 2 + last])[k] = gp;
           }
       }
-      // tile tables
-      size_t n_sym = 0, n_app = 0;
-      for (int i : members) {
-        const MatPlan& q = ctx->mats[i];
-        const size_t tm = q.mp / q.tile, tn = q.np / q.tile;
-        n_sym += tm * (tm + 1) / 2;
-        n_app += tm * tn;
-      }
-      g.tiles_sym = take(n_sym * sizeof(GemmTile));
-      g.tiles_apply = take(n_app * sizeof(GemmTile));
-      g.tiles_apply_last = take(n_app * sizeof(GemmTile));
-      {
+      // tile tables: level 1 = whole 256-tiles (bf16 only), level 0 = what they leave uncovered
+      for (int level = 1; level >= 0; --level) {
+        if (level == 1 && ns_dtype != MUON_BF16) continue;
         std::vector<std::vector<GemmTile>> sym(members.size()), app(members.size()), app_last(members.size());
+        size_t n_sym = 0, n_app = 0, n_last = 0;
         for (size_t k = 0; k < members.size(); ++k) {
           const MatPlan& q = ctx->mats[members[k]];
-          const int tm = q.mp / q.tile, tn = q.np / q.tile;
-          blocked_tiles((int32_t)k, tm, tm, true, sym[k]);
-          blocked_tiles((int32_t)k, tm, tn, false, app[k]);
-          if (swapped_last(q, ns_dtype))
-            blocked_tiles((int32_t)k, tn, tm, false, app_last[k]);
-          else
-            app_last[k] = app[k];
+          const int cm = ns_dtype == MUON_BF16 ? q.mp / kCoarse : 0, cn = ns_dtype == MUON_BF16 ? q.np / kCoarse : 0;
+          if (level == 1) {
+            blocked_tiles((int32_t)k, cm, cm, true, 0, 0, sym[k]);
+            blocked_tiles((int32_t)k, cm, cn, false, 0, 0, app[k]);
+            if (swapped_last(q, ns_dtype)) blocked_tiles((int32_t)k, cn, cm, false, 0, 0, app_last[k]);
+            else app_last[k] = app[k];
+          } else {
+            const int tm = q.mp / q.tile, tn = q.np / q.tile, r = kCoarse / q.tile;
+            blocked_tiles((int32_t)k, tm, tm, true, cm * r, cm * r, sym[k]);
+            blocked_tiles((int32_t)k, tm, tn, false, cm * r, cn * r, app[k]);
+            if (swapped_last(q, ns_dtype)) blocked_tiles((int32_t)k, tn, tm, false, cn * r, cm * r, app_last[k]);
+            else app_last[k] = app[k];
+          }
+          n_sym += sym[k].size();
+          n_app += app[k].size();
+          n_last += app_last[k].size();
         }
-        deal_tiles(sym, reinterpret_cast<GemmTile*>(img.data() + g.tiles_sym));
-        deal_tiles(app, reinterpret_cast<GemmTile*>(img.data() + g.tiles_apply));
-        deal_tiles(app_last, reinterpret_cast<GemmTile*>(img.data() + g.tiles_apply_last));
+        TileSet& ts = level ? g.coarse : g.fine;
+        ts.sym = take(n_sym * sizeof(GemmTile));
+        ts.apply = take(n_app * sizeof(GemmTile));
+        ts.apply_last = take(n_last * sizeof(GemmTile));
+        ts.n_sym = (int)deal_tiles(sym, reinterpret_cast<GemmTile*>(img.data() + ts.sym));
+        ts.n_apply = (int)deal_tiles(app, reinterpret_cast<GemmTile*>(img.data() + ts.apply));
+        ts.n_apply_last = (int)deal_tiles(app_last, reinterpret_cast<GemmTile*>(img.data() + ts.apply_last));
       }
-      g.n_tiles_sym = (int)n_sym;
-      g.n_tiles_apply = (int)n_app;
       ch.groups.push_back(g);
     }
   }
@@ -568,18 +563,35 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
       for (const Group& g : ch.groups) {
         auto P = [&](size_t o) { return reinterpret_cast<const GemmProblem*>(ctx->ws + o); };
         auto T = [&](size_t o) { return reinterpret_cast<const GemmTile*>(ctx->ws + o); };
-        if (bf) {
-          MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(g.shape, P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
-          MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(g.shape, P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
-          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(g.shape, P(g.prob_apply[par * 2 + last]),
-                                                            T(last ? g.tiles_apply_last : g.tiles_apply), g.n_tiles_apply, 1.f, a,
-                                                            first ? 0 : -1, s));
-        } else {
-          MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram), T(g.tiles_sym), g.n_tiles_sym, 1.f, 0.f, first ? 1 : -1, s));
-          MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(g.tiles_sym), g.n_tiles_sym, c, b, -1, s));
-          MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]),
-                                                           T(last ? g.tiles_apply_last : g.tiles_apply), g.n_tiles_apply, 1.f, a,
-                                                           first ? 0 : -1, s));
+        // one launch per product and block-tile size (256-tiles first, then the strips they leave)
+        for (int level = 1; level >= 0; --level) {
+          const TileSet& ts = level ? g.coarse : g.fine;
+          if (ts.n_sym == 0) continue;
+          if (bf)
+            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f,
+                                                        first ? 1 : -1, s));
+          else
+            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f, first ? 1 : -1, s));
+        }
+        for (int level = 1; level >= 0; --level) {
+          const TileSet& ts = level ? g.coarse : g.fine;
+          if (ts.n_sym == 0) continue;
+          if (bf)
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
+          else
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
+        }
+        for (int level = 1; level >= 0; --level) {
+          const TileSet& ts = level ? g.coarse : g.fine;
+          const size_t t_app = last ? ts.apply_last : ts.apply;
+          const int n_app = last ? ts.n_apply_last : ts.n_apply;
+          if (n_app == 0) continue;
+          if (bf)
+            MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_apply[par * 2 + last]), T(t_app),
+                                                              n_app, 1.f, a, first ? 0 : -1, s));
+          else
+            MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(t_app), n_app, 1.f, a,
+                                                             first ? 0 : -1, s));
         }
       }
     }
@@ -605,7 +617,8 @@ int muon_debug_read_update(muon_ctx* ctx, int32_t index, void* dst, int32_t dst_
 int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t cap) {
   if (!ctx || !out || index < 0 || index >= ctx->n || cap < 0) return MUON_E_INVALID_ARG;
   const MatPlan& q = ctx->mats[index];
-  const int64_t v[8] = {q.m, q.n, q.transposed, q.mp, q.np, q.chunk, q.tile, q.tile};
+  const int coarse = ctx->ns_dtype == MUON_BF16 && q.mp >= kCoarse ? kCoarse : q.tile;
+  const int64_t v[8] = {q.m, q.n, q.transposed, q.mp, q.np, q.chunk, coarse, q.tile};
   const int k = std::min<int>(cap, 8);
   for (int i = 0; i < k; ++i) out[i] = v[i];
   return k;

@@ -53,7 +53,7 @@ struct GemmProblem {
   const void* E;      // M x N addend at the output position (may be null), leading dimension lde
   const void* Et;     // the same addend stored transposed, N x M, leading dimension ldet (bf16 kernel reads this one)
   void* C;            // M x N output (may be null), leading dimension ldc
-  void* Ct;           // N x M transposed output (may be null), leading dimension ldct
+  void* Ct;           // N x M transposed output, leading dimension ldct (the bf16 kernel requires it unless symmetric)
   const float* scal;  // per-matrix scalars (alpha source)
   int32_t K;
   int32_t ldl, ldr, lde, ldet, ldc, ldct;
