@@ -27,6 +27,9 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 PEAK_F32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 DEFAULT_CONFIG = "block_w4096"
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
+# profiles/ (counter KiB x 1024 x copy-calibration factor 2.0 for fetch, 1.0 for write).  None = not measured.
+MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1495180 * 2.0 + 396732 * 1.0) * 1024)}
 
 
 def executed_ns_flops(wl, ns_steps, fine, coarse):
@@ -148,7 +151,7 @@ def main() -> int:
     else:
         avg_launch_ms, flops_per_launch, achieved = 0.0, 0.0, 0.0
     roofline = {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": None,
+                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if bf16 else None,
                 "kernel": "ns_gemm_bf16_kernel" if bf16 else "ns_gemm_f32_kernel",
                 "avg_launch_ms": avg_launch_ms, "launches_per_step": gemm_launches / max(args.steps, 1),
                 "nominal_flops_per_launch": flops_per_launch,
