@@ -71,12 +71,8 @@ struct TileCfg {
   static constexpr size_t lds_bytes(int nstage) { return lds_main(nstage); }
 };
 
-// s_waitcnt vmcnt(N) lgkmcnt(0): used in front of the barrier, where this wave's LDS reads must have returned too
-template <int N>
-__device__ __forceinline__ void wait_vmcnt_lgkm0() {
-  static_assert(N >= 0 && N < 64, "vmcnt range");
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
-}
+// s_waitcnt lgkmcnt(0), vmcnt untouched: this wave's LDS reads have returned
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8)); }
 
 #ifdef MUON_DBG_TIMING
 __device__ long long g_dbg_t[64 * 8];
@@ -103,7 +99,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   constexpr int STAGE_B = (BM + BN) * ROWB;        // bytes per stage
   constexpr int KSTEPS = BK / 16;                  // MFMA k-steps per slab
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
-  static_assert(NW % 2 == 0 && NSTAGE == 2 && NLOAD < 32 && FM % 2 == 0, "pipeline shape");
+  static_assert(NW % 2 == 0 && NSTAGE == 2 && NLOAD < 32, "pipeline shape");
   static_assert(4 * FM == WTM / 8 && (WTM / 8 & (WTM / 8 - 1)) == 0 && BM / 8 >= 16, "slot addressing: 4i+q and wm*WTM/8 use disjoint bits");
 
   extern __shared__ __align__(16) unsigned char smem[];
@@ -124,16 +120,28 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   const u16* lsrc = static_cast<const u16*>(p.L) + (size_t)(row0 + dma_row) * p.ldl + dma_chunk * 8;
   const u16* rsrc = static_cast<const u16*>(p.R) + (size_t)(col0 + dma_row) * p.ldr + dma_chunk * 8;
   const size_t lstep = (size_t)(8 * NW) * p.ldl, rstep = (size_t)(8 * NW) * p.ldr;
-  auto request = [&](int kt, int stage) {
+  // requests DMA instructions [first, first + count) of slab kt (instructions 0..LI-1 fetch L rows, the rest R rows)
+  auto request_part = [&](int kt, int stage, auto first_tag, auto count_tag) {
+    constexpr int FIRST = decltype(first_tag)::value, COUNT = decltype(count_tag)::value;
     unsigned char* base = smem + stage * STAGE_B + wave * 1024;
 #pragma unroll
-    for (int i = 0; i < LI; ++i)
-      __builtin_amdgcn_global_load_lds((gptr)(lsrc + i * lstep + (size_t)kt * BK), (lptr)(base + i * NW * 1024), 16, 0, 0);
-#pragma unroll
-    for (int i = 0; i < RI; ++i)
-      __builtin_amdgcn_global_load_lds((gptr)(rsrc + i * rstep + (size_t)kt * BK),
-                                       (lptr)(base + BM * ROWB + i * NW * 1024), 16, 0, 0);
+    for (int n = FIRST; n < FIRST + COUNT; ++n) {
+      if (n < LI)
+        __builtin_amdgcn_global_load_lds((gptr)(lsrc + n * lstep + (size_t)kt * BK), (lptr)(base + n * NW * 1024), 16, 0, 0);
+      else
+        __builtin_amdgcn_global_load_lds((gptr)(rsrc + (n - LI) * rstep + (size_t)kt * BK),
+                                         (lptr)(base + BM * ROWB + (n - LI) * NW * 1024), 16, 0, 0);
+    }
   };
+  // A slab's requests: HEAD of them in phase C, TAIL in each of the next iteration's phases A and B.  Measured:
+  // moving requests into A and B (already dense with fragment reads) costs more there than it saves in C.
+  constexpr int TAIL = 0, HEAD = NLOAD - 2 * TAIL;
+  using Zero = std::integral_constant<int, 0>;
+  using HeadN = std::integral_constant<int, HEAD>;
+  using TailA0 = std::integral_constant<int, HEAD>;
+  using TailB0 = std::integral_constant<int, HEAD + TAIL>;
+  using TailN = std::integral_constant<int, TAIL>;
+  using AllN = std::integral_constant<int, NLOAD>;
 
   // ---- fragment addressing: lane (r = lane%32, h = lane/32) reads logical chunk 2*kk + h of its row ----
   const int fr = lane & 31, fh = lane >> 5;
@@ -165,19 +173,17 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   };
   // ---- pipeline: two LDS stages.  A wave instruction that requests 1 KB keeps the wave's (in-order) issue port
   // busy until the memory pipeline accepts it - measured ~57 clocks each when 4 waves request 16 KB apiece in a
-  // burst - so requests are never issued in a burst: one request follows every second MFMA.  The loop is skewed
-  // by one k-step so that no MFMA ever waits for LDS latency.  Iteration kt (slab kt sits in stage `cur`):
-  //   A  MFMAs of k-step 3 of slab kt-1, interleaved with the fragment reads of k-steps 0..2 of slab kt
-  //   B  fragment reads of k-step 3, MFMAs of k-step 0; then barrier #1: nobody reads stage `cur` any more
-  //   C  MFMAs of k-steps 1 and 2, interleaved with the requests of slab kt+2 into stage `cur`
-  //      then wait until slab kt+1 (requested one iteration ago) has landed, barrier #2.
+  // burst - so requests are never issued in a burst: one request follows every second MFMA of phase C.  The
+  // loop is skewed by one k-step so that no MFMA ever waits for LDS latency.  Iteration kt (slab kt sits in
+  // stage `cur`, the other stage is `cur^1`):
+  //   A  MFMAs of k-step 3 of slab kt-1 | fragment reads of k-steps 0, 1 of slab kt
+  //   B  MFMAs of k-step 0              | fragment reads of k-steps 2, 3
+  //      barrier #1: nobody reads stage `cur` any more
+  //   C  MFMAs of k-steps 1, 2          | the requests of slab kt+2, into stage `cur`
+  //      wait until slab kt+1 (requested one iteration ago) has landed, barrier #2.
   const int KT = p.K / BK;
-  DBG_BLK(0);
-#ifdef MUON_DBG_TIMING
-  if (tid == 0 && blockIdx.x < 8192) g_dbg_clk[blockIdx.x * 2] = clock64();
-#endif
-  request(0, 0);
-  if (KT > 1) { request(1, 1); wait_vmcnt<NLOAD>(); } else { wait_vmcnt<0>(); }
+  request_part(0, 0, Zero{}, AllN{});
+  if (KT > 1) { request_part(1, 1, Zero{}, HeadN{}); wait_vmcnt<HEAD>(); } else { wait_vmcnt<0>(); }
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -212,33 +218,45 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 
   int cur = 0;
   int kt = 0;
-  // one iteration; REFILL: slab kt+2 exists and is requested; SYNC: slab kt+1 exists and must be visible afterwards
+  // one iteration; REFILL: slab kt+2 exists; SYNC: slab kt+1 exists (its last requests are issued here and it
+  // must be visible afterwards)
   auto iteration = [&](auto refill_tag, auto sync_tag) {
     constexpr bool REFILL = decltype(refill_tag)::value, SYNC = decltype(sync_tag)::value;
     DBG_T(0);
     // A
-#pragma unroll
-    for (int kk = 0; kk < KSTEPS - 1; ++kk) fread(cur, kk);
+    fread(cur, 0);
+    fread(cur, 1);
+    if (SYNC && TAIL > 0) request_part(kt + 1, cur ^ 1, TailA0{}, TailN{});
     mma(KSTEPS - 1);
 #pragma unroll
-    for (int g = 0; g < (KSTEPS - 1) * (FM + FN) / 3; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN * 3) / ((KSTEPS - 1) * (FM + FN)), 0);
+    for (int g = 0; g < FM + FN; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);
+      if (SYNC && TAIL > 0 && g % ((FM + FN) / (TAIL > 0 ? TAIL : 1)) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     DBG_T(1);
-    // B
-    fread(cur, KSTEPS - 1);
+    // B.  MFMAs go first: the LDS counter is only 4 bits wide, so a wait placed behind more than 15 younger reads
+    // degenerates into "wait for everything".
+    fread(cur, 2);
+    fread(cur, 3);
+    if (SYNC && TAIL > 0) request_part(kt + 1, cur ^ 1, TailB0{}, TailN{});
     mma(0);
-    __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+    for (int g = 0; g < FM + FN; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (SYNC && TAIL > 0 && g % ((FM + FN) / (TAIL > 0 ? TAIL : 1)) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
     __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);
     __builtin_amdgcn_sched_barrier(0);
     DBG_T(2);
     if (REFILL) {
-      wait_vmcnt_lgkm0<NLOAD>();                 // my fragment reads have returned (slab kt+1's requests may be in flight)
+      wait_lgkm0();                              // my fragment reads have returned
       __builtin_amdgcn_s_barrier();              // barrier #1: stage `cur` is free
       DBG_T(3);
-      request(kt + 2, cur);
+      request_part(kt + 2, cur, Zero{}, HeadN{});
     }
     // C
     if (!REFILL && !SYNC && Et) et_request(cur ^ 1);
@@ -253,15 +271,15 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     }
     if (REFILL) {
 #pragma unroll
-      for (int g = 0; g < NLOAD; ++g) {
-        __builtin_amdgcn_sched_group_barrier(0x008, ((KSTEPS - 2) * FM * FN) / NLOAD, 0);
+      for (int g = 0; g < HEAD; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, ((KSTEPS - 2) * FM * FN) / HEAD, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
     DBG_T(4);
     if (SYNC) {
-      if (REFILL) wait_vmcnt<NLOAD>(); else wait_vmcnt<0>();   // slab kt+1 has landed (slab kt+2 may be in flight)
+      if (REFILL) wait_vmcnt<HEAD>(); else wait_vmcnt<0>();   // slab kt+1 has landed (the head of slab kt+2 may be in flight)
       __builtin_amdgcn_s_barrier();              // barrier #2: ... for every wave
     }
     DBG_T(5);
