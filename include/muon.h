@@ -44,6 +44,14 @@ typedef enum {
   MUON_E_MISALIGNED = -7           /* a buffer pointer is not aligned to its element size              */
 } muon_status;
 
+/* The three ways of controlling the update RMS compared in section 3.1; the update is
+ * W_t = W_{t-1} - lr * (factor * O_t + weight_decay * W_{t-1}). */
+typedef enum {
+  MUON_SCALE_ADJUSTED_LR = 0,  /* factor = rms_scale * sqrt(max(A,B))   (Eq. 7 = Eq. 4, the paper's choice) */
+  MUON_SCALE_BASELINE = 1,     /* factor = rms_scale * sqrt(hidden_size) (Eq. 5)                             */
+  MUON_SCALE_UPDATE_NORM = 2   /* factor = rms_scale / RMS(O_t)          (Eq. 6; O_t = 0 gives factor 0)     */
+} muon_scale_mode;
+
 /* One 2-D parameter.  W, G and M are rows x cols, row-major, contiguous. */
 typedef struct {
   void* w;              /* device; weight W_{t-1}, dtype w_dtype; overwritten with W_t                 */
@@ -64,12 +72,15 @@ typedef struct {
   double eps;           /* added to ||U||_F; 0 reproduces the paper's formula, >0 guards an all-zero U */
   int32_t ns_steps;     /* N >= 0 (the paper uses 5)                         */
   int32_t nesterov;     /* 0: U = M_t;  1: U = mu*M_t + G                    */
+  int32_t scale_mode;   /* muon_scale_mode: which factor multiplies O in the update (section 3.1) */
+  int32_t reserved;     /* must be 0                                         */
+  double hidden_size;   /* H of the "Baseline" variant (Eq. 5); ignored by the other modes */
 } muon_hparams;
 
 typedef struct muon_ctx muon_ctx;
 
 /* Fills *hp with the paper's settings: mu 0.95, N 5, (a,b,c) above, rms_scale 0.2, nesterov 1,
- * eps 1e-7, lr 0, weight_decay 0. */
+ * eps 1e-7, lr 0, weight_decay 0, scale_mode MUON_SCALE_ADJUSTED_LR, hidden_size 0. */
 int muon_default_hparams(muon_hparams* hp);
 
 /*

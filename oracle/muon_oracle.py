@@ -94,17 +94,37 @@ def newton_schulz(U, steps: int = DEFAULT_NS_STEPS, a: float = NS_A, b: float = 
     return X.T.copy() if transposed else X
 
 
-def apply_update(W_prev, O, lr: float, weight_decay: float,
-                 rms_scale: float = DEFAULT_RMS_SCALE) -> np.ndarray:
-    """W_t = W_{t-1} - eta * (rms_scale * sqrt(max(A, B)) * O + lambda * W_{t-1}).
+def update_factor(O, shape, rms_scale: float = DEFAULT_RMS_SCALE, scale_mode: str = "adjusted_lr",
+                  hidden_size=None) -> float:
+    """The factor that multiplies O in the update, for the three variants of section 3.1.
 
-    Eq. 4 (which contains the decoupled weight decay of Eq. 3); rms_scale is the
-    paper's 0.2; [A, B] is the shape of the matrix as passed.
+    "adjusted_lr" (Eq. 7, identical to Eq. 4): rms_scale * sqrt(max(A, B));
+    "baseline"    (Eq. 5):                     rms_scale * sqrt(H), H the model's hidden size;
+    "update_norm" (Eq. 6):                     rms_scale / RMS(O)   (0 for O = 0).
+    """
+    A, B = shape
+    if scale_mode == "adjusted_lr":
+        return float(rms_scale) * float(np.sqrt(float(max(A, B))))
+    if scale_mode == "baseline":
+        return float(rms_scale) * float(np.sqrt(float(hidden_size)))
+    if scale_mode == "update_norm":
+        r = update_rms(O)
+        return float(rms_scale) / r if r > 0.0 else 0.0
+    raise ValueError(scale_mode)
+
+
+def apply_update(W_prev, O, lr: float, weight_decay: float, rms_scale: float = DEFAULT_RMS_SCALE,
+                 scale_mode: str = "adjusted_lr", hidden_size=None) -> np.ndarray:
+    """W_t = W_{t-1} - eta * (factor * O + lambda * W_{t-1}).
+
+    With the default mode this is Eq. 4 (which contains the decoupled weight decay of
+    Eq. 3): factor = rms_scale * sqrt(max(A, B)), rms_scale the paper's 0.2, [A, B] the
+    shape of the matrix as passed.  The other modes are Eq. 5 and Eq. 6.
     """
     W_prev = _f64(W_prev)
-    A, B = W_prev.shape
-    scale = float(rms_scale) * np.sqrt(float(max(A, B)))
-    return W_prev - float(lr) * (scale * _f64(O) + float(weight_decay) * W_prev)
+    O = _f64(O)
+    factor = update_factor(O, W_prev.shape, rms_scale, scale_mode, hidden_size)
+    return W_prev - float(lr) * (factor * O + float(weight_decay) * W_prev)
 
 
 def update_rms(O) -> float:
@@ -115,10 +135,11 @@ def update_rms(O) -> float:
 
 def muon_step(W_prev, G, M_prev, *, lr: float, weight_decay: float, mu: float = DEFAULT_MU,
               ns_steps: int = DEFAULT_NS_STEPS, a: float = NS_A, b: float = NS_B, c: float = NS_C,
-              rms_scale: float = DEFAULT_RMS_SCALE, eps: float = 0.0, nesterov: bool = True):
+              rms_scale: float = DEFAULT_RMS_SCALE, eps: float = 0.0, nesterov: bool = True,
+              scale_mode: str = "adjusted_lr", hidden_size=None):
     """One whole step on one matrix.  Returns (W_t, M_t, O_t) in float64."""
     M = momentum_update(M_prev, G, mu)
     U = ns_input(M, G, mu, nesterov)
     O = newton_schulz(U, ns_steps, a, b, c, eps)
-    W = apply_update(W_prev, O, lr, weight_decay, rms_scale)
+    W = apply_update(W_prev, O, lr, weight_decay, rms_scale, scale_mode, hidden_size)
     return W, M, O

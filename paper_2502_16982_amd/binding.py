@@ -14,6 +14,7 @@ import os
 from typing import Iterable, List, Optional, Sequence
 
 MUON_F32, MUON_BF16 = 0, 1
+MUON_SCALE_ADJUSTED_LR, MUON_SCALE_BASELINE, MUON_SCALE_UPDATE_NORM = 0, 1, 2
 MUON_OK = 0
 STATUS_NAMES = {
     0: "MUON_OK", -1: "MUON_E_INVALID_ARG", -2: "MUON_E_UNSUPPORTED_DTYPE", -3: "MUON_E_SHAPE_MISMATCH",
@@ -37,7 +38,8 @@ class muon_hparams(C.Structure):
     _fields_ = [("lr", C.c_double), ("weight_decay", C.c_double), ("momentum", C.c_double),
                 ("a", C.c_double), ("b", C.c_double), ("c", C.c_double),
                 ("rms_scale", C.c_double), ("eps", C.c_double),
-                ("ns_steps", C.c_int32), ("nesterov", C.c_int32)]
+                ("ns_steps", C.c_int32), ("nesterov", C.c_int32),
+                ("scale_mode", C.c_int32), ("reserved", C.c_int32), ("hidden_size", C.c_double)]
 
 
 class MuonError(RuntimeError):

@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void norm_finalize_kernel(const MatDesc* __res
 // ------------------------------------------------------------------------------------------------------
 // a8: W <- W - lr * (rms_scale*sqrt(max(A,B)) * O + wd * W), fp32 math, one rounding to W's dtype.
 // ------------------------------------------------------------------------------------------------------
-template <typename WT, typename XT>
+template <typename WT, typename XT, bool UPDATE>
 __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float lr, float wd,
                                            float scale, int o_sel, float* red) {
   const int tid = threadIdx.x;
@@ -224,7 +224,19 @@ __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, 
   if (r < A && c0 < B) {
     const size_t base = (size_t)r * (size_t)B + (size_t)c0;
     const XT* op = o + (size_t)r * pitch + c0;
-    if ((c0 + 16 <= B) && ((B & 7) == 0) && aligned16(w)) {
+    if (!UPDATE) {
+      if (c0 + 16 <= B) {
+        float ov[16];
+        load16<XT>(op, ov);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ss = fmaf(ov[i], ov[i], ss);
+      } else {
+        for (int i = 0; i < 16 && c0 + i < B; ++i) {
+          const float ov = load1<XT>(op + i);
+          ss = fmaf(ov, ov, ss);
+        }
+      }
+    } else if ((c0 + 16 <= B) && ((B & 7) == 0) && aligned16(w)) {
       float wv[16], ov[16];
       load16<WT>(w + base, wv);
       load16<XT>(op, ov);
@@ -252,25 +264,46 @@ __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, 
 template <typename XT>
 __global__ __launch_bounds__(256) void apply_update_kernel(const MatDesc* __restrict__ mats, const MatPtrs* __restrict__ ptrs,
                                                             const EwTile* __restrict__ tiles, float lr, float wd,
-                                                            float rms_scale, int o_sel, int use_s) {
+                                                            float rms_scale, int scale_mode, float sqrt_hidden, int o_sel,
+                                                            int use_s) {
   __shared__ float red[4];
   const EwTile t = tiles[blockIdx.x];
   const MatDesc d = mats[t.mat];
   const MatPtrs pt = ptrs[t.mat];
-  float scale = rms_scale * d.sqrt_max;
-  if (use_s) scale *= d.scal[0];
+  // factor that multiplies the stored O: the three variants of section 3.1 (Eq. 5-7)
+  float scale;
+  if (scale_mode == 2) {
+    scale = rms_scale * d.scal[2];              // 1/RMS of the stored O: any common factor of O cancels
+  } else {
+    scale = rms_scale * (scale_mode == 1 ? sqrt_hidden : d.sqrt_max);
+    if (use_s) scale *= d.scal[0];
+  }
   for (int k = 0; k < t.count; ++k) {
     if (k) __syncthreads();     // the reduction scratch is reused
     if (d.w_dtype == kDtypeBF16)
-      apply_tile<u16, XT>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
+      apply_tile<u16, XT, true>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
     else
-      apply_tile<float, XT>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
+      apply_tile<float, XT, true>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
+  }
+}
+
+// Per-tile sums of O^2 only (first pass of the "Update Norm" variant, Eq. 6).
+template <typename XT>
+__global__ __launch_bounds__(256) void update_sumsq_kernel(const MatDesc* __restrict__ mats, const EwTile* __restrict__ tiles,
+                                                            int o_sel) {
+  __shared__ float red[4];
+  const EwTile t = tiles[blockIdx.x];
+  const MatDesc d = mats[t.mat];
+  const MatPtrs none{nullptr, nullptr, nullptr};
+  for (int k = 0; k < t.count; ++k) {
+    if (k) __syncthreads();
+    apply_tile<float, XT, false>(d, none, t.tr, t.tc + k, 0.f, 0.f, 0.f, o_sel, red);
   }
 }
 
 // sqrt(mean(O^2)) per matrix from the per-tile sums left by apply_update_kernel.
 __global__ __launch_bounds__(256) void update_rms_kernel(const MatDesc* __restrict__ mats, int first_mat, int use_s,
-                                                          float* __restrict__ out) {
+                                                          int to_scal, float* __restrict__ out) {
   __shared__ double red[256];
   const MatDesc d = mats[first_mat + blockIdx.x];
   double acc = 0.0;
@@ -283,8 +316,12 @@ __global__ __launch_bounds__(256) void update_rms_kernel(const MatDesc* __restri
   }
   if (threadIdx.x == 0) {
     double rms = sqrt(red[0] / ((double)d.rows * (double)d.cols));
-    if (use_s) rms *= (double)d.scal[0];
-    out[first_mat + blockIdx.x] = (float)rms;
+    if (to_scal) {
+      d.scal[2] = rms > 0.0 ? (float)(1.0 / rms) : 0.f;
+    } else {
+      if (use_s) rms *= (double)d.scal[0];
+      out[first_mat + blockIdx.x] = (float)rms;
+    }
   }
 }
 
@@ -321,18 +358,28 @@ hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, 
 }
 
 hipError_t launch_apply_update(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles, float lr, float wd,
-                               float rms_scale, int o_sel, int use_s, int ns_dtype, hipStream_t s) {
+                               float rms_scale, int scale_mode, float sqrt_hidden, int o_sel, int use_s, int ns_dtype,
+                               hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
   if (ns_dtype == kDtypeBF16)
-    apply_update_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, o_sel, use_s);
+    apply_update_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, scale_mode, sqrt_hidden, o_sel, use_s);
   else
-    apply_update_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, o_sel, use_s);
+    apply_update_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, scale_mode, sqrt_hidden, o_sel, use_s);
   return hipGetLastError();
 }
 
-hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int use_s, float* out, hipStream_t s) {
+hipError_t launch_update_sumsq(const MatDesc* mats, const EwTile* tiles, int n_tiles, int o_sel, int ns_dtype, hipStream_t s) {
+  if (n_tiles <= 0) return hipSuccess;
+  if (ns_dtype == kDtypeBF16)
+    update_sumsq_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, tiles, o_sel);
+  else
+    update_sumsq_kernel<float><<<n_tiles, 256, 0, s>>>(mats, tiles, o_sel);
+  return hipGetLastError();
+}
+
+hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int use_s, int to_scal, float* out, hipStream_t s) {
   if (n_mats <= 0) return hipSuccess;
-  update_rms_kernel<<<n_mats, 256, 0, s>>>(mats, first_mat, use_s, out);
+  update_rms_kernel<<<n_mats, 256, 0, s>>>(mats, first_mat, use_s, to_scal, out);
   return hipGetLastError();
 }
 

@@ -275,6 +275,9 @@ int muon_default_hparams(muon_hparams* hp) {
   hp->eps = 1e-7;
   hp->ns_steps = 5;
   hp->nesterov = 1;
+  hp->scale_mode = MUON_SCALE_ADJUSTED_LR;
+  hp->reserved = 0;
+  hp->hidden_size = 0.0;
   return MUON_OK;
 }
 
@@ -518,7 +521,8 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
   if (n != ctx->n) return MUON_E_SHAPE_MISMATCH;
   if (hp->ns_steps < 0 || !(hp->eps >= 0.0) || !std::isfinite(hp->lr) || !std::isfinite(hp->weight_decay) ||
       !std::isfinite(hp->momentum) || !std::isfinite(hp->a) || !std::isfinite(hp->b) || !std::isfinite(hp->c) ||
-      !std::isfinite(hp->rms_scale))
+      !std::isfinite(hp->rms_scale) || hp->scale_mode < MUON_SCALE_ADJUSTED_LR || hp->scale_mode > MUON_SCALE_UPDATE_NORM ||
+      hp->reserved != 0 || (hp->scale_mode == MUON_SCALE_BASELINE && !(hp->hidden_size > 0.0 && std::isfinite(hp->hidden_size))))
     return MUON_E_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
@@ -595,9 +599,16 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
         }
       }
     }
+    if (hp->scale_mode == MUON_SCALE_UPDATE_NORM) {
+      // Eq. 6 needs RMS(O) before the update: one extra pass over O
+      MUON_TIMED(MUON_PROF_RMS, launch_update_sumsq(ctx->d_mats, ew, ch.n_ew_tiles, o_sel, ctx->ns_dtype, s));
+      MUON_TIMED(MUON_PROF_RMS, launch_update_rms(ctx->d_mats, ch.first, ch.count, use_s, 1, nullptr, s));
+    }
     MUON_TIMED(MUON_PROF_UPDATE, launch_apply_update(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->lr,
-                                                     (float)hp->weight_decay, (float)hp->rms_scale, o_sel, use_s, ctx->ns_dtype, s));
-    if (update_rms_out) MUON_TIMED(MUON_PROF_RMS, launch_update_rms(ctx->d_mats, ch.first, ch.count, use_s, update_rms_out, s));
+                                                     (float)hp->weight_decay, (float)hp->rms_scale, hp->scale_mode,
+                                                     (float)std::sqrt(hp->hidden_size > 0.0 ? hp->hidden_size : 0.0), o_sel, use_s,
+                                                     ctx->ns_dtype, s));
+    if (update_rms_out) MUON_TIMED(MUON_PROF_RMS, launch_update_rms(ctx->d_mats, ch.first, ch.count, use_s, 0, update_rms_out, s));
   }
   ctx->last_o_sel = o_sel;
   ctx->last_use_s = use_s;

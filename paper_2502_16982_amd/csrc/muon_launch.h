@@ -30,12 +30,18 @@ hipError_t launch_gemm_f32(const GemmProblem* probs, const GemmTile* tiles, int 
 // a8: W <- W - lr*(scale*O + wd*W); also leaves per-tile sums of O^2 in the partials.
 // o_sel: which buffer holds O in W's orientation for transposed matrices (Xt[o_sel]); use_s: multiply O by
 // scal[0] (only when no Newton-Schulz iteration ran).
+// scale_mode: 0 factor = rms_scale*sqrt(max(A,B)); 1 factor = rms_scale*sqrt_hidden; 2 factor = rms_scale*scal[2]
+// (scal[2] = 1/RMS of the stored O, left there by launch_update_rms(..., to_scal = 1)).
 hipError_t launch_apply_update(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles,
-                               float lr, float wd, float rms_scale, int o_sel, int use_s, int ns_dtype,
-                               hipStream_t s);
+                               float lr, float wd, float rms_scale, int scale_mode, float sqrt_hidden, int o_sel,
+                               int use_s, int ns_dtype, hipStream_t s);
 
-// sqrt(mean(O^2)) per matrix from the partials left by apply_update.
-hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int use_s, float* out, hipStream_t s);
+// Per-tile sums of O^2 into the partials, without touching W (first pass of the "Update Norm" variant).
+hipError_t launch_update_sumsq(const MatDesc* mats, const EwTile* tiles, int n_tiles, int o_sel, int ns_dtype, hipStream_t s);
+
+// From the per-tile sums of O^2: to_scal = 0 writes sqrt(mean(O^2)) per matrix to out; to_scal = 1 writes
+// 1/sqrt(mean(stored O^2)) (0 when O = 0) to scal[2].
+hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int use_s, int to_scal, float* out, hipStream_t s);
 
 // Test hook: O of one matrix -> dst (rows x cols contiguous).
 hipError_t launch_read_update(const MatDesc* mats, int mat, int o_sel, int use_s, int ns_dtype, void* dst,

@@ -19,15 +19,20 @@ def to64(t: torch.Tensor) -> np.ndarray:
 
 def hp_from(h: workloads.Hyper, **over):
     d = dict(lr=h.lr, weight_decay=h.weight_decay, momentum=h.momentum, a=h.a, b=h.b, c=h.c,
-             rms_scale=h.rms_scale, eps=h.eps, ns_steps=h.ns_steps, nesterov=int(h.nesterov))
+             rms_scale=h.rms_scale, eps=h.eps, ns_steps=h.ns_steps, nesterov=int(h.nesterov),
+             scale_mode=binding.MUON_SCALE_ADJUSTED_LR, hidden_size=0.0)
     d.update(over)
     return binding.default_hparams(**d), d
+
+
+SCALE_MODE_NAMES = {0: "adjusted_lr", 1: "baseline", 2: "update_norm"}
 
 
 def oracle_step(w0, g0, m0, d):
     return orc.muon_step(w0, g0, m0, lr=d["lr"], weight_decay=d["weight_decay"], mu=d["momentum"],
                          ns_steps=d["ns_steps"], a=d["a"], b=d["b"], c=d["c"], rms_scale=d["rms_scale"],
-                         eps=d["eps"], nesterov=bool(d["nesterov"]))
+                         eps=d["eps"], nesterov=bool(d["nesterov"]), scale_mode=SCALE_MODE_NAMES[d.get("scale_mode", 0)],
+                         hidden_size=d.get("hidden_size") or None)
 
 
 def rel_fro(x: np.ndarray, ref: np.ndarray) -> float:
@@ -59,10 +64,11 @@ def bf16_ulp(x64: np.ndarray) -> np.ndarray:
 
 def check_weight_update(w_gpu: torch.Tensor, w0: np.ndarray, o_gpu: np.ndarray, d) -> dict:
     """Apply stage alone: feed the library's own O to the oracle's update rule and compare W."""
-    ref = orc.apply_update(w0, o_gpu, d["lr"], d["weight_decay"], d["rms_scale"])
+    mode = SCALE_MODE_NAMES[d.get("scale_mode", 0)]
+    ref = orc.apply_update(w0, o_gpu, d["lr"], d["weight_decay"], d["rms_scale"], mode, d.get("hidden_size") or None)
     got = to64(w_gpu)
-    A, B = w0.shape
-    scale = np.abs(w0) * (1 + abs(d["lr"] * d["weight_decay"])) + abs(d["lr"] * d["rms_scale"]) * np.sqrt(max(A, B)) * np.abs(o_gpu)
+    factor = orc.update_factor(o_gpu, w0.shape, d["rms_scale"], mode, d.get("hidden_size") or None)
+    scale = np.abs(w0) * (1 + abs(d["lr"] * d["weight_decay"])) + abs(d["lr"] * factor) * np.abs(o_gpu)
     if w_gpu.dtype == torch.float32:
         err = np.abs(got - ref) / np.maximum(scale, 1e-300)
         return {"max_rel": float(err.max()), "frac_off": 0.0}

@@ -36,13 +36,14 @@ def test_library_exports_every_declared_symbol(binding):
 
 def test_struct_layout_matches_header(binding):
     assert C.sizeof(binding.muon_param) == 3 * 8 + 2 * 8 + 2 * 4
-    assert C.sizeof(binding.muon_hparams) == 8 * 8 + 2 * 4
+    assert C.sizeof(binding.muon_hparams) == 8 * 8 + 4 * 4 + 8
 
 
 def test_default_hparams_are_the_papers(binding):
     hp = binding.default_hparams()
     assert (hp.a, hp.b, hp.c) == (3.4445, -4.7750, 2.0315)
     assert hp.momentum == 0.95 and hp.ns_steps == 5 and hp.rms_scale == 0.2 and hp.nesterov == 1
+    assert hp.scale_mode == binding.MUON_SCALE_ADJUSTED_LR and hp.reserved == 0 and hp.hidden_size == 0.0
 
 
 def test_status_strings(binding):

@@ -103,6 +103,36 @@ def test_other_coefficients_and_hyperparameters(dev):
     assert_records(U.run_and_compare(wl, dev, steps=2, hp_over=over), U.TOL_F32_FRO)
 
 
+@pytest.mark.parametrize("mode", [binding.MUON_SCALE_BASELINE, binding.MUON_SCALE_UPDATE_NORM])
+def test_update_scaling_variants(dev, mode):
+    """Eq. 5 (0.2 sqrt(H)) and Eq. 6 (0.2 O / RMS(O)) of section 3.1, fp32 and bf16 weights, both orientations."""
+    over = {"scale_mode": mode, "hidden_size": 192.0, "lr": 0.05}
+    wl = workloads.custom("variants", [(192, 320), (320, 192), (100, 100)], seed_base=28)
+    assert_records(U.run_and_compare(wl, dev, steps=2, hp_over=over), U.TOL_BF16_FRO)
+    wl32 = workloads.custom("variants32", [(96, 160), (160, 96)], w_dtype=torch.float32, g_dtype=torch.float32, ns_dtype="f32",
+                            w_std=1.0, g_std=1.0, seed_base=29)
+    assert_records(U.run_and_compare(wl32, dev, steps=2, hp_over=over), U.TOL_F32_FRO)
+    if mode == binding.MUON_SCALE_UPDATE_NORM:
+        # the applied update has RMS exactly rms_scale: W0 = 0, lambda = 0, lr = 1  ->  RMS(W1) = 0.2
+        w = torch.zeros(200, 136, device=dev)
+        g = torch.randn(200, 136, device=dev)
+        m = torch.zeros_like(w)
+        for ns, ns_steps in (("f32", 5), ("bf16", 5), ("bf16", 0)):
+            w.zero_(); m.zero_()
+            st = binding.MuonStepper([(w, g, m)], ns_dtype=ns)
+            st.step(binding.default_hparams(lr=1.0, weight_decay=0.0, scale_mode=mode, ns_steps=ns_steps))
+            torch.cuda.synchronize()
+            assert float(w.double().pow(2).mean().sqrt()) == pytest.approx(0.2, rel=2e-6)
+            st.close()
+        # an all-zero update stays zero (factor 0, no NaN)
+        w.fill_(1.0); m.zero_()
+        st = binding.MuonStepper([(w, torch.zeros_like(g), m)], ns_dtype="f32")
+        st.step(binding.default_hparams(lr=0.5, weight_decay=0.0, scale_mode=mode))
+        torch.cuda.synchronize()
+        assert torch.equal(w, torch.ones_like(w))
+        st.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # degenerate inputs
 # ---------------------------------------------------------------------------------------------
@@ -222,6 +252,12 @@ def test_error_codes_with_a_live_context(dev):
     bad = binding.default_hparams(ns_steps=-1)
     assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
     bad = binding.default_hparams(lr=float("nan"))
+    assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
+    bad = binding.default_hparams(scale_mode=3)
+    assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
+    bad = binding.default_hparams(scale_mode=binding.MUON_SCALE_BASELINE, hidden_size=0.0)
+    assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
+    bad = binding.default_hparams(reserved=1)
     assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
     dst = torch.empty(64, 96, device=dev)
     assert L.muon_debug_read_update(st.ctx, 0, C.c_void_p(dst.data_ptr()), 0, None) == -6   # no step yet

@@ -290,6 +290,41 @@ def test_apply_update_degenerate_hyperparameters():
     assert np.allclose(d, -0.2 * 3.0) and np.allclose(dt, -0.2 * 3.0)
 
 
+def test_update_scaling_variants():
+    """Eq. 5-7 of section 3.1.  Update Norm makes the RMS of the applied update exactly rms_scale; Baseline equals
+    Adjusted LR when max(A, B) = H and differs from it by sqrt(max(A, B) / H) otherwise."""
+    rng = np.random.default_rng(14)
+    W = rng.standard_normal((6, 24))
+    O = rng.standard_normal((6, 24)) * 0.3
+    zero = np.zeros_like(W)
+    # Update Norm: with lambda = 0, lr = 1 the weight change is the scaled update itself
+    d = orc.apply_update(zero, O, 1.0, 0.0, 0.2, "update_norm")
+    assert math.sqrt(float(np.mean(d ** 2))) == pytest.approx(0.2, rel=1e-14)
+    assert np.max(np.abs(d + 0.2 * O / math.sqrt(float(np.mean(O ** 2))))) < 1e-15
+    assert np.array_equal(orc.apply_update(W, zero, 0.5, 0.0, 0.2, "update_norm"), W)        # O = 0: no update, no NaN
+    # scale invariance of Update Norm in O
+    assert np.max(np.abs(orc.apply_update(W, 7.0 * O, 0.1, 0.01, 0.2, "update_norm") -
+                         orc.apply_update(W, O, 0.1, 0.01, 0.2, "update_norm"))) < 1e-14
+    # Baseline vs Adjusted LR
+    adj = orc.apply_update(zero, O, 1.0, 0.0, 0.2, "adjusted_lr")
+    assert np.max(np.abs(orc.apply_update(zero, O, 1.0, 0.0, 0.2, "baseline", hidden_size=24) - adj)) < 1e-15
+    base6 = orc.apply_update(zero, O, 1.0, 0.0, 0.2, "baseline", hidden_size=6)
+    assert np.max(np.abs(base6 * 2.0 - adj)) < 1e-14                                         # sqrt(24 / 6) = 2
+    for i in range(6):
+        for j in range(24):
+            assert base6[i, j] == pytest.approx(-(0.2 * math.sqrt(6.0) * O[i, j]), rel=1e-15)
+    # weight decay is untouched by the mode
+    for mode, h in (("adjusted_lr", None), ("baseline", 9.0), ("update_norm", None)):
+        assert np.max(np.abs(orc.apply_update(W, zero, 0.5, 0.1, 0.2, mode, h) - W * (1 - 0.05))) < 1e-15
+    with pytest.raises(ValueError):
+        orc.update_factor(O, (6, 24), 0.2, "nope")
+    # for the exact polar factor all three coincide when H = max(A, B) (Lemma 1: RMS = 1/sqrt(max(A, B)))
+    U, _, Vt = np.linalg.svd(rng.standard_normal((6, 24)), full_matrices=False)
+    P = U @ Vt
+    a = orc.apply_update(zero, P, 1.0, 0.0, 0.2, "adjusted_lr")
+    assert np.max(np.abs(orc.apply_update(zero, P, 1.0, 0.0, 0.2, "update_norm") - a)) < 1e-14
+
+
 # ----------------------------------------------------------------------------------------------
 # whole step
 # ----------------------------------------------------------------------------------------------
