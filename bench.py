@@ -94,6 +94,31 @@ def cpu_baseline(wl, budget_s=25.0):
             "gflops": flops_done / t_done / 1e9}
 
 
+def bench_adamw(dev, steps=5):
+    """HBM rate of the AdamW kernel on the non-matrix parameters of a width-2048 model (embedding and LM head of
+    163840 x 2048 bf16, 55 RMSNorm gains), timed with events on the launch stream."""
+    import torch
+    from paper_2502_16982_amd import binding
+    sizes = [163840 * 2048, 163840 * 2048] + [2048] * 55
+    tensors = []
+    for n in sizes:
+        tensors.append((torch.empty(n, dtype=torch.bfloat16, device=dev).normal_(0, 0.02),
+                        torch.empty(n, dtype=torch.bfloat16, device=dev).normal_(0, 1e-3),
+                        torch.zeros(n, dtype=torch.float32, device=dev), torch.zeros(n, dtype=torch.float32, device=dev)))
+    stream = torch.cuda.current_stream(dev)
+    binding.muon_adamw_step(tensors, lr=4.2e-4, weight_decay=0.1, step=1, stream_ptr=stream.cuda_stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for t in range(steps):
+        binding.muon_adamw_step(tensors, lr=4.2e-4, weight_decay=0.1, step=2 + t, stream_ptr=stream.cuda_stream)
+    e1.record(stream)
+    e1.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    n_el = sum(sizes)
+    gbs = n_el * 22 / (ms * 1e-3) / 1e9      # p 2+2, g 2, m 4+4, v 4+4 bytes per element
+    return {"elements": n_el, "ms_per_step": ms, "algorithmic_GBs": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -188,6 +213,8 @@ def main() -> int:
     }
     st.close()
     del tensors
+    torch.cuda.empty_cache()
+    out["adamw_non_matrix_params"] = bench_adamw(dev)
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

@@ -152,6 +152,33 @@ enum {
 int muon_profile_enable(muon_ctx* ctx, int enable);
 int muon_profile_read(muon_ctx* ctx, double* ms_out, int64_t* launches_out, int reset);
 
+/*
+ * AdamW for the parameters that stay off Muon (RMSNorm gains, LM head, embeddings: section 2.2, "Matching update
+ * RMS of AdamW"), sharing lr and weight decay with it:
+ *   m = beta1 m + (1-beta1) g;  v = beta2 v + (1-beta2) g^2;
+ *   p = p - lr * ( m/(1-beta1^t) / (sqrt(v/(1-beta2^t)) + eps) + weight_decay * p ).
+ * Tensors are flat arrays of `numel` elements (any shape); p and g may be fp32 or bf16, the moments m and v
+ * are fp32 and updated in place.  Stateless: needs no context and no workspace (pointers travel in kernel
+ * arguments, 24 tensors per launch).  Asynchronous on hip_stream.  `step` is t, counted from 1.
+ */
+typedef struct {
+  void* p;            /* device; parameter, dtype p_dtype; updated in place   */
+  const void* g;      /* device; gradient, dtype g_dtype; read only           */
+  float* m;           /* device; first moment, fp32; updated in place         */
+  float* v;           /* device; second moment, fp32; updated in place        */
+  int64_t numel;      /* number of elements (>= 1)                            */
+  int32_t p_dtype;    /* muon_dtype                                           */
+  int32_t g_dtype;    /* muon_dtype                                           */
+} muon_adamw_param;
+
+typedef struct {
+  double lr, weight_decay;   /* shared with Muon                               */
+  double beta1, beta2, eps;  /* 0 <= beta < 1; eps >= 0                        */
+  int64_t step;              /* t >= 1                                         */
+} muon_adamw_hparams;
+
+int muon_adamw_step(const muon_adamw_param* params, int32_t n, const muon_adamw_hparams* hp, void* hip_stream);
+
 /* Releases host-side state.  The workspace is the caller's to free afterwards. */
 void muon_destroy(muon_ctx* ctx);
 

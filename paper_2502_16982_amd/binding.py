@@ -24,7 +24,7 @@ STATUS_NAMES = {
 EXPORTS = (
     "muon_default_hparams", "muon_workspace_bytes", "muon_init", "muon_step", "muon_debug_read_update",
     "muon_plan_describe", "muon_plan_chunks", "muon_destroy", "muon_status_string", "muon_last_hip_error",
-    "muon_profile_enable", "muon_profile_read",
+    "muon_profile_enable", "muon_profile_read", "muon_adamw_step",
 )
 PROF_NAMES = ("momentum_norm_cast", "norm_finalize", "gram", "poly", "apply_poly", "weight_update", "update_rms")
 
@@ -40,6 +40,16 @@ class muon_hparams(C.Structure):
                 ("rms_scale", C.c_double), ("eps", C.c_double),
                 ("ns_steps", C.c_int32), ("nesterov", C.c_int32),
                 ("scale_mode", C.c_int32), ("reserved", C.c_int32), ("hidden_size", C.c_double)]
+
+
+class muon_adamw_param(C.Structure):
+    _fields_ = [("p", C.c_void_p), ("g", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("numel", C.c_int64), ("p_dtype", C.c_int32), ("g_dtype", C.c_int32)]
+
+
+class muon_adamw_hparams(C.Structure):
+    _fields_ = [("lr", C.c_double), ("weight_decay", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double),
+                ("eps", C.c_double), ("step", C.c_int64)]
 
 
 class MuonError(RuntimeError):
@@ -93,6 +103,8 @@ def lib() -> C.CDLL:
     L.muon_status_string.restype = C.c_char_p
     L.muon_last_hip_error.argtypes = []
     L.muon_last_hip_error.restype = C.c_int
+    L.muon_adamw_step.argtypes = [P(muon_adamw_param), C.c_int32, P(muon_adamw_hparams), C.c_void_p]
+    L.muon_adamw_step.restype = C.c_int
     L.muon_profile_enable.argtypes = [C.c_void_p, C.c_int]
     L.muon_profile_enable.restype = C.c_int
     L.muon_profile_read.argtypes = [C.c_void_p, P(C.c_double), P(C.c_int64), C.c_int]
@@ -180,6 +192,26 @@ def muon_profile_read(ctx, reset: bool = False) -> dict:
     cnt = (C.c_int64 * len(PROF_NAMES))()
     _check(lib().muon_profile_read(ctx, ms, cnt, int(bool(reset))), "muon_profile_read")
     return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(PROF_NAMES)}
+
+
+def muon_adamw_step(tensors, *, lr: float, weight_decay: float, beta1: float = 0.9, beta2: float = 0.95,
+                    eps: float = 1e-8, step: int = 1, stream_ptr: int = 0) -> None:
+    """tensors: iterable of (p, g, m, v) torch tensors of one size each (any shape, contiguous)."""
+    tensors = [tuple(t) for t in tensors]
+    arr = (muon_adamw_param * max(len(tensors), 1))()
+    for i, (p, g, m, v) in enumerate(tensors):
+        if not (p.is_contiguous() and g.is_contiguous() and m.is_contiguous() and v.is_contiguous()):
+            raise MuonError(-1, f"tensor {i}: buffers must be contiguous")
+        if not (p.numel() == g.numel() == m.numel() == v.numel()):
+            raise MuonError(-1, f"tensor {i}: p, g, m, v must have one size")
+        if dtype_code(m.dtype) != MUON_F32 or dtype_code(v.dtype) != MUON_F32:
+            raise MuonError(-2, f"tensor {i}: moments must be fp32")
+        a = arr[i]
+        a.p, a.g, a.m, a.v = p.data_ptr(), g.data_ptr(), m.data_ptr(), v.data_ptr()
+        a.numel = p.numel()
+        a.p_dtype, a.g_dtype = dtype_code(p.dtype), dtype_code(g.dtype)
+    hp = muon_adamw_hparams(lr, weight_decay, beta1, beta2, eps, step)
+    _check(lib().muon_adamw_step(arr, len(tensors), C.byref(hp), C.c_void_p(stream_ptr)), "muon_adamw_step")
 
 
 def muon_destroy(ctx) -> None:

@@ -668,6 +668,48 @@ int muon_profile_read(muon_ctx* ctx, double* ms_out, int64_t* launches_out, int 
   return MUON_OK;
 }
 
+int muon_adamw_step(const muon_adamw_param* params, int32_t n, const muon_adamw_hparams* hp, void* hip_stream) {
+  if (!params || !hp || n <= 0) return MUON_E_INVALID_ARG;
+  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0) || !(hp->beta2 >= 0.0 && hp->beta2 < 1.0) || !(hp->eps >= 0.0) || hp->step < 1 ||
+      !std::isfinite(hp->lr) || !std::isfinite(hp->weight_decay) || !std::isfinite(hp->eps))
+    return MUON_E_INVALID_ARG;
+  for (int i = 0; i < n; ++i) {
+    const muon_adamw_param& q = params[i];
+    if (!q.p || !q.g || !q.m || !q.v || q.numel < 1) return MUON_E_INVALID_ARG;
+    if ((q.p_dtype != MUON_F32 && q.p_dtype != MUON_BF16) || (q.g_dtype != MUON_F32 && q.g_dtype != MUON_BF16))
+      return MUON_E_UNSUPPORTED_DTYPE;
+    const uintptr_t pa = q.p_dtype == MUON_BF16 ? 1u : 3u, ga = q.g_dtype == MUON_BF16 ? 1u : 3u;
+    if ((reinterpret_cast<uintptr_t>(q.p) & pa) || (reinterpret_cast<uintptr_t>(q.g) & ga) ||
+        (reinterpret_cast<uintptr_t>(q.m) & 3u) || (reinterpret_cast<uintptr_t>(q.v) & 3u))
+      return MUON_E_MISALIGNED;
+    if (adamw_blocks_for(q.numel) > (1ll << 30)) return MUON_E_INVALID_ARG;
+  }
+  // bias corrections in double, handed to the kernel as reciprocals
+  const float inv_bc1 = (float)(1.0 / (1.0 - std::pow(hp->beta1, (double)hp->step)));
+  const float inv_bc2 = (float)(1.0 / (1.0 - std::pow(hp->beta2, (double)hp->step)));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  for (int first = 0; first < n;) {
+    AdamwBatch b{};
+    long long blocks = 0;
+    int k = 0;
+    while (first + k < n && k < kAdamwSlots && blocks + adamw_blocks_for(params[first + k].numel) <= (1ll << 30)) {
+      const muon_adamw_param& q = params[first + k];
+      b.p[k] = q.p; b.g[k] = q.g; b.m[k] = q.m; b.v[k] = q.v;
+      b.numel[k] = q.numel;
+      b.p_dtype[k] = q.p_dtype; b.g_dtype[k] = q.g_dtype;
+      b.block_start[k] = (int)blocks;
+      blocks += adamw_blocks_for(q.numel);
+      ++k;
+    }
+    b.block_start[k] = (int)blocks;
+    b.n = k;
+    MUON_HIP(launch_adamw(b, (int)blocks, (float)hp->lr, (float)hp->weight_decay, (float)hp->beta1, (float)hp->beta2,
+                          (float)hp->eps, inv_bc1, inv_bc2, s));
+    first += k;
+  }
+  return MUON_OK;
+}
+
 int muon_plan_chunks(const muon_ctx* ctx) { return ctx ? (int)ctx->chunks.size() : MUON_E_INVALID_ARG; }
 
 void muon_destroy(muon_ctx* ctx) {

@@ -47,4 +47,20 @@ hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int
 hipError_t launch_read_update(const MatDesc* mats, int mat, int o_sel, int use_s, int ns_dtype, void* dst,
                               int dst_dtype, hipStream_t s);
 
+// AdamW (non-matrix parameters): up to kAdamwSlots tensors per launch, passed by value in the kernel arguments.
+constexpr int kAdamwSlots = 24;
+struct AdamwBatch {
+  void* p[kAdamwSlots];
+  const void* g[kAdamwSlots];
+  float* m[kAdamwSlots];
+  float* v[kAdamwSlots];
+  long long numel[kAdamwSlots];
+  int block_start[kAdamwSlots + 1];   // first block of each tensor; [n] = total blocks
+  int p_dtype[kAdamwSlots], g_dtype[kAdamwSlots];
+  int n;
+};
+long long adamw_blocks_for(long long numel);
+hipError_t launch_adamw(const AdamwBatch& batch, int n_blocks, float lr, float wd, float beta1, float beta2, float eps,
+                        float inv_bc1, float inv_bc2, hipStream_t s);
+
 }  // namespace muon
