@@ -42,6 +42,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(1))) void* gptr;
 typedef __attribute__((address_space(3))) void* lptr;
+typedef __attribute__((address_space(1))) u32x4* gvec_ptr;   // 16-byte global store target (keeps the stores off the flat path)
 
 constexpr int BK = 64;        // K slab in elements: one 128-byte line per row, the request size the L1 serves at full rate
 constexpr int ROWB = 128;     // bytes per LDS row of a pipeline stage (BK bf16, unpadded, swizzled)
@@ -394,7 +395,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
       for (int u = 0; u < SB; ++u) {
         const int i = i0 + u;
-        *reinterpret_cast<u32x4*>(dst[i % PERIOD] + (size_t)(i / PERIOD) * dstep) = v[u];
+        *(gvec_ptr)(dst[i % PERIOD] + (size_t)(i / PERIOD) * dstep) = v[u];
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -458,7 +459,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
       for (int u = 0; u < SB; ++u) {
         const int i = i0 + u;
-        *reinterpret_cast<u32x4*>(dst[i % PERIOD] + (size_t)(i / PERIOD) * dstep) = v[u];
+        *(gvec_ptr)(dst[i % PERIOD] + (size_t)(i / PERIOD) * dstep) = v[u];
       }
       __builtin_amdgcn_sched_barrier(0);
     }
