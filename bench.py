@@ -216,6 +216,16 @@ def main() -> int:
     torch.cuda.empty_cache()
     out["adamw_non_matrix_params"] = bench_adamw(dev)
     torch.cuda.empty_cache()
+    if bf16:
+        # Context for roofline.frac (which stays priced against the published peak): what the matrix cores sustain
+        # on register-resident operands right now, on this chip, with random and with all-zero operand values.
+        rnd = binding.muon_probe_mfma_rate(True)
+        zer = binding.muon_probe_mfma_rate(False)
+        out["roofline"]["mfma_register_loop"] = {
+            "random_operands_tflops": rnd["tflops"], "random_operands_clock_mhz": rnd["clock_mhz"],
+            "zero_operands_tflops": zer["tflops"], "zero_operands_clock_mhz": zer["clock_mhz"],
+            "executed_frac_of_random_operand_rate": (out["roofline"]["executed_tflops"] / rnd["tflops"]) if rnd["tflops"] else None,
+            "nominal_frac_of_random_operand_rate": (out["roofline"]["achieved"] / rnd["tflops"]) if rnd["tflops"] else None}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)

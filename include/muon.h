@@ -179,6 +179,19 @@ typedef struct {
 
 int muon_adamw_step(const muon_adamw_param* params, int32_t n, const muon_adamw_hparams* hp, void* hip_stream);
 
+/*
+ * Measurement aid (not part of the optimizer path; Section 2.1's Newton-Schulz products are what it prices):
+ * runs the bf16 matrix-core instruction and register blocking of the Newton-Schulz GEMMs with operands that never
+ * leave registers, one 256-thread block per compute unit, and reports the sustained rate.  That rate bounds every
+ * bf16 GEMM on the device; it depends on the operand values (random_operands != 0: uniform in (-1, 1); 0: all
+ * zeros) because the chip lowers its clock under switching load.
+ *   iters          loop trips, 32 MFMAs per wave each (1 .. 2^20); 40000 runs about 20 ms
+ *   tflops_out     host pointer, receives TFLOP/s          clock_mhz_out  host pointer, receives the mean core clock
+ * Allocates and frees a few KB of device memory, launches on the default stream of the current device and waits.
+ * Returns MUON_OK, MUON_E_INVALID_ARG or MUON_E_HIP.
+ */
+int muon_probe_mfma_rate(int random_operands, int iters, double* tflops_out, double* clock_mhz_out);
+
 /* Releases host-side state.  The workspace is the caller's to free afterwards. */
 void muon_destroy(muon_ctx* ctx);
 

@@ -24,7 +24,7 @@ STATUS_NAMES = {
 EXPORTS = (
     "muon_default_hparams", "muon_workspace_bytes", "muon_init", "muon_step", "muon_debug_read_update",
     "muon_plan_describe", "muon_plan_chunks", "muon_destroy", "muon_status_string", "muon_last_hip_error",
-    "muon_profile_enable", "muon_profile_read", "muon_adamw_step",
+    "muon_profile_enable", "muon_profile_read", "muon_adamw_step", "muon_probe_mfma_rate",
 )
 PROF_NAMES = ("momentum_norm_cast", "norm_finalize", "gram", "poly", "apply_poly", "weight_update", "update_rms")
 
@@ -109,6 +109,8 @@ def lib() -> C.CDLL:
     L.muon_profile_enable.restype = C.c_int
     L.muon_profile_read.argtypes = [C.c_void_p, P(C.c_double), P(C.c_int64), C.c_int]
     L.muon_profile_read.restype = C.c_int
+    L.muon_probe_mfma_rate.argtypes = [C.c_int, C.c_int, P(C.c_double), P(C.c_double)]
+    L.muon_probe_mfma_rate.restype = C.c_int
     _LIB = L
     return L
 
@@ -116,6 +118,14 @@ def lib() -> C.CDLL:
 def _check(status: int, where: str) -> None:
     if status != MUON_OK:
         raise MuonError(status, where)
+
+
+def muon_probe_mfma_rate(random_operands: bool = True, iters: int = 40000) -> dict:
+    """Sustained bf16 matrix-core rate with register-resident operands: {"tflops", "clock_mhz"}."""
+    tf, mhz = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().muon_probe_mfma_rate(1 if random_operands else 0, int(iters), C.byref(tf), C.byref(mhz)),
+           "muon_probe_mfma_rate")
+    return {"tflops": tf.value, "clock_mhz": mhz.value}
 
 
 def dtype_code(torch_dtype) -> int:

@@ -9,7 +9,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_NAME = "libmuon_hip.so"
 LIB_PATH = os.path.join(PKG_DIR, LIB_NAME)
-SOURCES = ("muon_api.hip", "kernels_ew.hip", "kernels_gemm_bf16.hip", "kernels_gemm_f32.hip", "kernels_adamw.hip")
+SOURCES = ("muon_api.hip", "kernels_ew.hip", "kernels_gemm_bf16.hip", "kernels_gemm_f32.hip", "kernels_adamw.hip",
+           "probe_mfma.hip")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
