@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 DEFAULT_CONFIG = "block_w4096"
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counter KiB x 1024 x copy-calibration factor 2.0 for fetch, 1.0 for write).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1495180 * 2.0 + 396732 * 1.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1520252 * 2.0 + 396732 * 1.0) * 1024)}
 
 
 def executed_ns_flops(wl, ns_steps, fine, coarse):
