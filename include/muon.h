@@ -75,6 +75,9 @@ typedef struct {
   int32_t scale_mode;   /* muon_scale_mode: which factor multiplies O in the update (section 3.1) */
   int32_t reserved;     /* must be 0                                         */
   double hidden_size;   /* H of the "Baseline" variant (Eq. 5); ignored by the other modes */
+  const double* coeff_schedule; /* null (the paper: one triple for all iterations), or a HOST array of 3*ns_steps
+                                   doubles, iteration k of Eq. 2 using (a,b,c) = [3k], [3k+1], [3k+2] instead of
+                                   a, b, c above; read during the call, not kept                              */
 } muon_hparams;
 
 typedef struct muon_ctx muon_ctx;

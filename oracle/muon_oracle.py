@@ -64,21 +64,27 @@ def frobenius_normalize(U, eps: float = 0.0) -> np.ndarray:
 
 
 def newton_schulz_iterate(X0, steps: int = DEFAULT_NS_STEPS,
-                          a: float = NS_A, b: float = NS_B, c: float = NS_C) -> np.ndarray:
+                          a: float = NS_A, b: float = NS_B, c: float = NS_C, schedule=None) -> np.ndarray:
     """N applications of Eq. 2:  X_k = a X + b (X X^T) X + c (X X^T)^2 X.
 
     Written exactly as printed: the Gram matrix X X^T, its square, and the three
     terms summed.  Works for any shape (the formula never transposes).
+
+    ``schedule`` (an extension; the paper uses one triple throughout): a sequence of
+    ``steps`` triples (a_k, b_k, c_k), iteration k using the k-th one instead of (a, b, c).
     """
     X = _f64(X0).copy()
-    for _ in range(int(steps)):
+    if schedule is not None and len(schedule) != int(steps):
+        raise ValueError("schedule needs one (a, b, c) triple per iteration")
+    for k in range(int(steps)):
+        ak, bk, ck = (a, b, c) if schedule is None else (float(v) for v in schedule[k])
         XXt = X @ X.T
-        X = a * X + b * (XXt @ X) + c * ((XXt @ XXt) @ X)
+        X = ak * X + bk * (XXt @ X) + ck * ((XXt @ XXt) @ X)
     return X
 
 
 def newton_schulz(U, steps: int = DEFAULT_NS_STEPS, a: float = NS_A, b: float = NS_B,
-                  c: float = NS_C, eps: float = 0.0, orient: bool = True) -> np.ndarray:
+                  c: float = NS_C, eps: float = 0.0, orient: bool = True, schedule=None) -> np.ndarray:
     """O = Newton-Schulz(U): normalise, orient so rows <= cols, iterate, orient back.
 
     The paper never transposes; because the quintic is odd, iterating on U^T and
@@ -90,7 +96,7 @@ def newton_schulz(U, steps: int = DEFAULT_NS_STEPS, a: float = NS_A, b: float = 
     transposed = orient and U.shape[0] > U.shape[1]
     if transposed:
         X0 = X0.T
-    X = newton_schulz_iterate(X0, steps, a, b, c)
+    X = newton_schulz_iterate(X0, steps, a, b, c, schedule)
     return X.T.copy() if transposed else X
 
 
@@ -136,10 +142,10 @@ def update_rms(O) -> float:
 def muon_step(W_prev, G, M_prev, *, lr: float, weight_decay: float, mu: float = DEFAULT_MU,
               ns_steps: int = DEFAULT_NS_STEPS, a: float = NS_A, b: float = NS_B, c: float = NS_C,
               rms_scale: float = DEFAULT_RMS_SCALE, eps: float = 0.0, nesterov: bool = True,
-              scale_mode: str = "adjusted_lr", hidden_size=None):
+              scale_mode: str = "adjusted_lr", hidden_size=None, schedule=None):
     """One whole step on one matrix.  Returns (W_t, M_t, O_t) in float64."""
     M = momentum_update(M_prev, G, mu)
     U = ns_input(M, G, mu, nesterov)
-    O = newton_schulz(U, ns_steps, a, b, c, eps)
+    O = newton_schulz(U, ns_steps, a, b, c, eps, schedule=schedule)
     W = apply_update(W_prev, O, lr, weight_decay, rms_scale, scale_mode, hidden_size)
     return W, M, O

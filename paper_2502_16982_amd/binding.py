@@ -39,7 +39,8 @@ class muon_hparams(C.Structure):
                 ("a", C.c_double), ("b", C.c_double), ("c", C.c_double),
                 ("rms_scale", C.c_double), ("eps", C.c_double),
                 ("ns_steps", C.c_int32), ("nesterov", C.c_int32),
-                ("scale_mode", C.c_int32), ("reserved", C.c_int32), ("hidden_size", C.c_double)]
+                ("scale_mode", C.c_int32), ("reserved", C.c_int32), ("hidden_size", C.c_double),
+                ("coeff_schedule", C.POINTER(C.c_double))]
 
 
 class muon_adamw_param(C.Structure):
@@ -143,8 +144,27 @@ def default_hparams(**overrides) -> muon_hparams:
     for k, v in overrides.items():
         if not hasattr(hp, k):
             raise AttributeError(k)
-        setattr(hp, k, v)
+        if k == "coeff_schedule":
+            set_coeff_schedule(hp, v)
+        else:
+            setattr(hp, k, v)
     return hp
+
+
+def set_coeff_schedule(hp: muon_hparams, schedule) -> None:
+    """Attach per-iteration (a, b, c) triples (or None) to hp; sets ns_steps to their number.  The host array is
+    kept alive by hp itself."""
+    if schedule is None:
+        hp.coeff_schedule = C.POINTER(C.c_double)()
+        hp._schedule_keepalive = None
+        return
+    flat = [float(x) for triple in schedule for x in triple]
+    if len(flat) % 3 or any(len(t) != 3 for t in schedule):
+        raise ValueError("schedule must be a sequence of (a, b, c) triples")
+    arr = (C.c_double * len(flat))(*flat)
+    hp._schedule_keepalive = arr
+    hp.coeff_schedule = C.cast(arr, C.POINTER(C.c_double))
+    hp.ns_steps = len(flat) // 3
 
 
 def param_array(shapes: Sequence[Sequence[int]], w_dtypes: Sequence[int], g_dtypes: Sequence[int]):

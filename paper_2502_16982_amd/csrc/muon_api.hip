@@ -278,6 +278,7 @@ int muon_default_hparams(muon_hparams* hp) {
   hp->scale_mode = MUON_SCALE_ADJUSTED_LR;
   hp->reserved = 0;
   hp->hidden_size = 0.0;
+  hp->coeff_schedule = nullptr;
   return MUON_OK;
 }
 
@@ -553,8 +554,10 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
   const int N = hp->ns_steps;
   const int use_s = N == 0;
   const int o_sel = N & 1;
-  const float a = (float)hp->a, b = (float)hp->b, c = (float)hp->c;
   const bool bf = ctx->ns_dtype == MUON_BF16;
+  if (hp->coeff_schedule)
+    for (int i = 0; i < 3 * N; ++i)
+      if (!std::isfinite(hp->coeff_schedule[i])) return MUON_E_INVALID_ARG;
 
   for (size_t ci = 0; ci < ctx->chunks.size(); ++ci) {
     const Chunk& ch = ctx->chunks[ci];
@@ -564,6 +567,8 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
     MUON_TIMED(MUON_PROF_NORM, launch_norm_finalize(ctx->d_mats, ch.first, ch.count, hp->eps, s));
     for (int it = 0; it < N; ++it) {
       const int first = it == 0, last = it == N - 1, par = it & 1;
+      const double* sch = hp->coeff_schedule ? hp->coeff_schedule + 3 * it : nullptr;
+      const float a = (float)(sch ? sch[0] : hp->a), b = (float)(sch ? sch[1] : hp->b), c = (float)(sch ? sch[2] : hp->c);
       for (const Group& g : ch.groups) {
         auto P = [&](size_t o) { return reinterpret_cast<const GemmProblem*>(ctx->ws + o); };
         auto T = [&](size_t o) { return reinterpret_cast<const GemmTile*>(ctx->ws + o); };

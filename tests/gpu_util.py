@@ -22,6 +22,8 @@ def hp_from(h: workloads.Hyper, **over):
              rms_scale=h.rms_scale, eps=h.eps, ns_steps=h.ns_steps, nesterov=int(h.nesterov),
              scale_mode=binding.MUON_SCALE_ADJUSTED_LR, hidden_size=0.0)
     d.update(over)
+    if d.get("coeff_schedule") is not None:
+        d["ns_steps"] = len(d["coeff_schedule"])
     return binding.default_hparams(**d), d
 
 
@@ -32,7 +34,7 @@ def oracle_step(w0, g0, m0, d):
     return orc.muon_step(w0, g0, m0, lr=d["lr"], weight_decay=d["weight_decay"], mu=d["momentum"],
                          ns_steps=d["ns_steps"], a=d["a"], b=d["b"], c=d["c"], rms_scale=d["rms_scale"],
                          eps=d["eps"], nesterov=bool(d["nesterov"]), scale_mode=SCALE_MODE_NAMES[d.get("scale_mode", 0)],
-                         hidden_size=d.get("hidden_size") or None)
+                         hidden_size=d.get("hidden_size") or None, schedule=d.get("coeff_schedule"))
 
 
 def rel_fro(x: np.ndarray, ref: np.ndarray) -> float:

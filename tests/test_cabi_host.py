@@ -36,7 +36,7 @@ def test_library_exports_every_declared_symbol(binding):
 
 def test_struct_layout_matches_header(binding):
     assert C.sizeof(binding.muon_param) == 3 * 8 + 2 * 8 + 2 * 4
-    assert C.sizeof(binding.muon_hparams) == 8 * 8 + 4 * 4 + 8
+    assert C.sizeof(binding.muon_hparams) == 8 * 8 + 4 * 4 + 8 + 8
 
 
 def test_default_hparams_are_the_papers(binding):

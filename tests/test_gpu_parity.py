@@ -103,6 +103,23 @@ def test_other_coefficients_and_hyperparameters(dev):
     assert_records(U.run_and_compare(wl, dev, steps=2, hp_over=over), U.TOL_F32_FRO)
 
 
+def test_coefficient_schedule(dev):
+    """Iteration k of Eq. 2 with its own (a, b, c): three steps with the paper's triple, then two with the textbook
+    order-5 Newton-Schulz polynomial (15, -10, 3)/8; also checks that the order of the triples is honoured."""
+    paper = (3.4445, -4.7750, 2.0315)
+    polish = (15.0 / 8.0, -10.0 / 8.0, 3.0 / 8.0)
+    sched = [paper, paper, paper, polish, polish]
+    wl = workloads.custom("sched", [(192, 320), (320, 192), (256, 256)], seed_base=41)
+    assert_records(U.run_and_compare(wl, dev, hp_over={"coeff_schedule": sched}), U.TOL_BF16_FRO)
+    assert_records(U.run_and_compare(wl, dev, hp_over={"coeff_schedule": sched[::-1]}), U.TOL_BF16_FRO)
+    wl32 = workloads.custom("sched32", [(96, 160), (160, 96)], w_dtype=torch.float32, g_dtype=torch.float32, ns_dtype="f32",
+                            w_std=1.0, g_std=1.0, seed_base=42)
+    assert_records(U.run_and_compare(wl32, dev, steps=2, hp_over={"coeff_schedule": sched}), U.TOL_F32_FRO)
+    assert_records(U.run_and_compare(wl32, dev, hp_over={"coeff_schedule": sched[::-1]}), U.TOL_F32_FRO)
+    # an even number of iterations leaves O in the other ping-pong buffer
+    assert_records(U.run_and_compare(wl32, dev, hp_over={"coeff_schedule": sched[:4]}), U.TOL_F32_FRO)
+
+
 @pytest.mark.parametrize("mode", [binding.MUON_SCALE_BASELINE, binding.MUON_SCALE_UPDATE_NORM])
 def test_update_scaling_variants(dev, mode):
     """Eq. 5 (0.2 sqrt(H)) and Eq. 6 (0.2 O / RMS(O)) of section 3.1, fp32 and bf16 weights, both orientations."""
@@ -258,6 +275,9 @@ def test_error_codes_with_a_live_context(dev):
     bad = binding.default_hparams(scale_mode=binding.MUON_SCALE_BASELINE, hidden_size=0.0)
     assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
     bad = binding.default_hparams(reserved=1)
+    assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
+    bad = binding.default_hparams(coeff_schedule=[(3.4445, -4.7750, 2.0315), (1.0, float("inf"), 0.0)])
+    assert bad.ns_steps == 2
     assert L.muon_step(st.ctx, st.params, 1, C.byref(bad), None, None) == -1
     dst = torch.empty(64, 96, device=dev)
     assert L.muon_debug_read_update(st.ctx, 0, C.c_void_p(dst.data_ptr()), 0, None) == -6   # no step yet

@@ -416,3 +416,78 @@ def test_planted_mistakes_are_caught_by_the_closed_form(name):
     for _ in range(5):
         X = step(X, A_, B_, C_)
     assert np.max(np.abs(X - svd_closed_form(M, 5))) > 1e-3
+
+
+# ----------------------------------------------------------------------------------------------
+# per-iteration coefficient schedule (extension of Eq. 2: iteration k uses its own triple)
+# ----------------------------------------------------------------------------------------------
+POLISH = (15.0 / 8.0, -10.0 / 8.0, 3.0 / 8.0)     # textbook order-5 Newton-Schulz polynomial (fixed point exactly 1)
+MIXED_SCHEDULE = [(A_, B_, C_), (A_, B_, C_), (A_, B_, C_), POLISH, POLISH]
+
+
+def svd_closed_form_schedule(M, schedule):
+    U, S, Vt = np.linalg.svd(np.asarray(M, dtype=np.float64), full_matrices=False)
+    S = S / math.sqrt(float(np.sum(S * S)))
+    for a, b, c in schedule:
+        S = quintic(S, a, b, c)
+    return (U * S) @ Vt
+
+
+@pytest.mark.parametrize("shape", [(5, 8), (8, 5), (7, 7), (1, 6)])
+def test_schedule_matches_composed_scalar_polynomials(shape):
+    rng = np.random.default_rng(31)
+    M = rng.standard_normal(shape)
+    O = orc.newton_schulz(M, steps=len(MIXED_SCHEDULE), schedule=MIXED_SCHEDULE)
+    assert np.max(np.abs(O - svd_closed_form_schedule(M, MIXED_SCHEDULE))) < 1e-11
+    # the order of the triples matters, and the closed form sees it
+    rev = MIXED_SCHEDULE[::-1]
+    O_rev = orc.newton_schulz(M, steps=len(rev), schedule=rev)
+    assert np.max(np.abs(O_rev - svd_closed_form_schedule(M, rev))) < 1e-11
+    assert np.max(np.abs(O_rev - O)) > 1e-4
+
+
+def test_constant_schedule_is_the_plain_iteration():
+    rng = np.random.default_rng(32)
+    M = rng.standard_normal((6, 10))
+    plain = orc.newton_schulz(M, steps=4)
+    assert np.array_equal(orc.newton_schulz(M, steps=4, schedule=[(A_, B_, C_)] * 4), plain)
+
+
+def test_schedule_position_k_is_used_by_iteration_k():
+    """Identity triples (1, 0, 0) everywhere except position j: the result is ONE real step, whichever j."""
+    rng = np.random.default_rng(33)
+    M = rng.standard_normal((4, 7))
+    one = orc.newton_schulz(M, steps=1)
+    for j in range(4):
+        sched = [(1.0, 0.0, 0.0)] * 4
+        sched[j] = (A_, B_, C_)
+        assert np.max(np.abs(orc.newton_schulz(M, steps=4, schedule=sched) - one)) < 1e-14
+    # two different real steps do not commute with each other's position
+    s01 = [(A_, B_, C_), POLISH]
+    assert np.max(np.abs(orc.newton_schulz(M, steps=2, schedule=s01) - svd_closed_form_schedule(M, s01))) < 1e-12
+
+
+def test_polishing_steps_pull_singular_values_to_one():
+    """After the paper's five steps the singular values sit in [0.68, 1.21]; the textbook polynomial maps that band
+    monotonically towards 1 (p(1) = 1, p'(1) = 0), so a few appended polishing steps give a near-orthogonal O."""
+    rng = np.random.default_rng(34)
+    M = rng.standard_normal((16, 24))
+    sched = [(A_, B_, C_)] * 5 + [POLISH] * 4
+    O = orc.newton_schulz(M, steps=len(sched), schedule=sched)
+    sv = np.linalg.svd(O, compute_uv=False)
+    assert np.max(np.abs(sv - 1.0)) < 1e-6
+    assert np.max(np.abs(O @ O.T - np.eye(16))) < 1e-5
+
+
+def test_schedule_of_wrong_length_is_rejected():
+    with pytest.raises(ValueError):
+        orc.newton_schulz(np.ones((2, 3)), steps=3, schedule=[(A_, B_, C_)] * 2)
+
+
+def test_whole_step_with_schedule_uses_it():
+    rng = np.random.default_rng(35)
+    W, G, M0 = rng.standard_normal((3, 5, 9)) * np.array([0.02, 1e-3, 1e-3])[:, None, None]
+    Wt, Mt, O = orc.muon_step(W, G, M0, lr=0.02, weight_decay=0.1, ns_steps=len(MIXED_SCHEDULE), schedule=MIXED_SCHEDULE)
+    U = 0.95 * Mt + G
+    assert np.max(np.abs(O - svd_closed_form_schedule(U, MIXED_SCHEDULE))) < 1e-11
+    assert np.max(np.abs(Wt - (W - 0.02 * (0.2 * math.sqrt(9) * O + 0.1 * W)))) < 1e-15
