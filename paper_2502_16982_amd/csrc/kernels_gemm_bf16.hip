@@ -75,6 +75,9 @@ struct TileCfg {
 // s_waitcnt lgkmcnt(0), vmcnt untouched: this wave's LDS reads have returned
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8)); }
 
+// Optional timing probes, compiled in only with -DMUON_DBG_TIMING (never in the library build): per block
+// {start, main loop done, block done} wall-clock stamps (100 MHz) plus the hardware id of the compute unit, and
+// core-clock stamps of the pipeline phases and epilogue stages of one block.  A host harness reads the symbols.
 #ifdef MUON_DBG_TIMING
 __device__ long long g_dbg_t[64 * 8];
 __device__ long long g_dbg_blk[8192 * 4];
@@ -111,6 +114,10 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN_, wn = wave % WN_;
   const int row0 = tile.ti * BM, col0 = tile.tj * BN;
+  DBG_BLK(0);
+#ifdef MUON_DBG_TIMING
+  if (tid == 0 && blockIdx.x < 8192) g_dbg_clk[blockIdx.x * 2] = clock64();
+#endif
 
   // ---- DMA addressing: a wave instruction fills 8 rows x 128 B; lane i -> slot (row i/8, chunk position i%8).
   // Position s of row R holds logical chunk s ^ ((R/2)%8); R = 8*(instruction index) + i/8 and the instruction
