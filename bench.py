@@ -27,9 +27,13 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 PEAK_F32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 DEFAULT_CONFIG = "block_w4096"
+OTHER_WORKLOADS = ("block_w4096", "dense12_w1024", "moe_bank_66x2048x1408")
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counter KiB x 1024 x copy-calibration factor 2.0 for fetch, 1.0 for write).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1520252 * 2.0 + 396732 * 1.0) * 1024)}
+MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1520252 * 2.0 + 396732 * 1.0) * 1024),
+                          "dense12_w1024": int((276719 * 2.0 + 356954 * 1.0) * 1024),
+                          # 256x256-tile launches only (the 128x128 strip launches move another 1.24 GB each)
+                          "moe_bank_66x2048x1408": int((1135010 * 2.0 + 1049140 * 1.0) * 1024)}
 
 
 def executed_ns_flops(wl, ns_steps, fine, coarse):
@@ -119,6 +123,75 @@ def bench_adamw(dev, steps=5):
     return {"elements": n_el, "ms_per_step": ms, "algorithmic_GBs": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
 
 
+def time_workload(name, steps, warmup, max_ws_gib, dev):
+    """W untimed warm-up steps, then exactly `steps` timed steps of the whole hot path over workload `name`
+    (inputs generated on the device beforehand), bracketed by device synchronisation.  Per-kernel-class times come
+    from HIP events the library records around every launch on the step's stream inside the timed region."""
+    import torch
+    from paper_2502_16982_amd import binding, workloads
+    wl = workloads.workload(name)
+    h = wl.hyper
+    tensors = workloads.make_all(wl, dev)
+    st = binding.MuonStepper(tensors, ns_dtype=wl.ns_dtype, max_workspace_bytes=int(max_ws_gib * 2 ** 30))
+    hp = binding.default_hparams(lr=h.lr, weight_decay=h.weight_decay, momentum=h.momentum, eps=h.eps,
+                                 ns_steps=h.ns_steps, nesterov=int(h.nesterov))
+    stream = torch.cuda.current_stream(dev)
+
+    for _ in range(warmup):
+        st.step(hp, stream=stream)
+    torch.cuda.synchronize()
+    binding.muon_profile_enable(st.ctx, True)
+    binding.muon_profile_read(st.ctx, reset=True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        st.step(hp, stream=stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = binding.muon_profile_read(st.ctx, reset=True)
+    binding.muon_profile_enable(st.ctx, False)
+
+    ms_per_step = elapsed * 1e3 / steps
+    nominal = wl.ns_flops()
+    gemm_ms = sum(prof[k][0] for k in ("gram", "poly", "apply_poly"))
+    gemm_launches = sum(prof[k][1] for k in ("gram", "poly", "apply_poly"))
+    executed = executed_ns_flops(wl, h.ns_steps, 128 if wl.ns_dtype == "bf16" else 64, 256 if wl.ns_dtype == "bf16" else 0)
+
+    bf16 = wl.ns_dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_VALU_TFLOPS
+    if gemm_launches:
+        avg_launch_ms = gemm_ms / gemm_launches
+        flops_per_launch = nominal * steps / gemm_launches
+        achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    else:
+        avg_launch_ms, flops_per_launch, achieved = 0.0, 0.0, 0.0
+    roofline = {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if bf16 else None,
+                "kernel": "ns_gemm_bf16_kernel" if bf16 else "ns_gemm_f32_kernel",
+                "avg_launch_ms": avg_launch_ms, "launches_per_step": gemm_launches / max(steps, 1),
+                "nominal_flops_per_launch": flops_per_launch,
+                "executed_tflops": executed * steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0,
+                "executed_frac": executed * steps / (gemm_ms * 1e-3) / 1e12 / peak if gemm_ms else 0.0}
+
+    n_el = wl.n_elements
+    g_b = 2 if wl.g_dtype == torch.bfloat16 else 4
+    w_b = 2 if wl.w_dtype == torch.bfloat16 else 4
+    x_b = 2 if bf16 else 4
+    ew = {}
+    for key, bytes_per_el in (("momentum_norm_cast", g_b + 8 + x_b), ("weight_update", 2 * w_b + x_b)):
+        ms, cnt = prof[key]
+        if cnt:
+            ew[key] = {"ms_per_step": ms / steps, "algorithmic_GBs": n_el * bytes_per_el * steps / (ms * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": n_el * bytes_per_el * steps / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+    chunks, ws_bytes = binding.muon_plan_chunks(st.ctx), st.workspace_bytes
+    st.close()
+    del tensors
+    torch.cuda.empty_cache()
+    return {"wl": wl, "hyper": h, "bf16": bf16, "elapsed": elapsed, "ms_per_step": ms_per_step, "nominal": nominal,
+            "executed": executed, "gemm_ms": gemm_ms, "prof": prof, "roofline": roofline, "elementwise": ew, "n_el": n_el,
+            "chunks": chunks, "workspace_bytes": ws_bytes}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,6 +199,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default=DEFAULT_CONFIG)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="time only --config, not the other workloads as well")
     ap.add_argument("--max-workspace-gib", type=float, default=16.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -140,59 +214,10 @@ def main() -> int:
         return 2
     binding.lib()
     dev = torch.device("cuda:0")
-    wl = workloads.workload(args.config)
-    h = wl.hyper
-    tensors = workloads.make_all(wl, dev)
-    st = binding.MuonStepper(tensors, ns_dtype=wl.ns_dtype, max_workspace_bytes=int(args.max_workspace_gib * 2 ** 30))
-    hp = binding.default_hparams(lr=h.lr, weight_decay=h.weight_decay, momentum=h.momentum, eps=h.eps,
-                                 ns_steps=h.ns_steps, nesterov=int(h.nesterov))
-    stream = torch.cuda.current_stream(dev)
-
-    for _ in range(args.warmup):
-        st.step(hp, stream=stream)
-    torch.cuda.synchronize()
-    binding.muon_profile_enable(st.ctx, True)
-    binding.muon_profile_read(st.ctx, reset=True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        st.step(hp, stream=stream)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof = binding.muon_profile_read(st.ctx, reset=True)
-    binding.muon_profile_enable(st.ctx, False)
-
-    ms_per_step = elapsed * 1e3 / args.steps
-    nominal = wl.ns_flops()
-    gemm_ms = sum(prof[k][0] for k in ("gram", "poly", "apply_poly"))
-    gemm_launches = sum(prof[k][1] for k in ("gram", "poly", "apply_poly"))
-    executed = executed_ns_flops(wl, h.ns_steps, 128 if wl.ns_dtype == "bf16" else 64, 256 if wl.ns_dtype == "bf16" else 0)
-
-    bf16 = wl.ns_dtype == "bf16"
-    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_VALU_TFLOPS
-    if gemm_launches:
-        avg_launch_ms = gemm_ms / gemm_launches
-        flops_per_launch = nominal * args.steps / gemm_launches
-        achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
-    else:
-        avg_launch_ms, flops_per_launch, achieved = 0.0, 0.0, 0.0
-    roofline = {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if bf16 else None,
-                "kernel": "ns_gemm_bf16_kernel" if bf16 else "ns_gemm_f32_kernel",
-                "avg_launch_ms": avg_launch_ms, "launches_per_step": gemm_launches / max(args.steps, 1),
-                "nominal_flops_per_launch": flops_per_launch,
-                "executed_tflops": executed * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0,
-                "executed_frac": executed * args.steps / (gemm_ms * 1e-3) / 1e12 / peak if gemm_ms else 0.0}
-
-    n_el = wl.n_elements
-    g_b = 2 if wl.g_dtype == torch.bfloat16 else 4
-    w_b = 2 if wl.w_dtype == torch.bfloat16 else 4
-    x_b = 2 if bf16 else 4
-    ew = {}
-    for key, bytes_per_el in (("momentum_norm_cast", g_b + 8 + x_b), ("weight_update", 2 * w_b + x_b)):
-        ms, cnt = prof[key]
-        if cnt:
-            ew[key] = {"ms_per_step": ms / args.steps, "algorithmic_GBs": n_el * bytes_per_el * args.steps / (ms * 1e-3) / 1e9,
-                       "frac_of_hbm_peak": n_el * bytes_per_el * args.steps / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    r = time_workload(args.config, args.steps, args.warmup, args.max_workspace_gib, dev)
+    wl, h, bf16 = r["wl"], r["hyper"], r["bf16"]
+    elapsed, ms_per_step, nominal, executed = r["elapsed"], r["ms_per_step"], r["nominal"], r["executed"]
+    gemm_ms, prof, roofline, ew, n_el = r["gemm_ms"], r["prof"], r["roofline"], r["elementwise"], r["n_el"]
 
     out = {
         "metric": "muon_steps_per_sec", "value": args.steps / elapsed, "unit": "steps/s",
@@ -202,7 +227,7 @@ def main() -> int:
         "config": {"workload": wl.name, "matrices": len(wl.shapes), "elements": n_el,
                    "w_dtype": str(wl.w_dtype).replace("torch.", ""), "g_dtype": str(wl.g_dtype).replace("torch.", ""),
                    "momentum_dtype": "float32", "ns_steps": h.ns_steps, "nesterov": bool(h.nesterov),
-                   "chunks": binding.muon_plan_chunks(st.ctx), "workspace_bytes": st.workspace_bytes},
+                   "chunks": r["chunks"], "workspace_bytes": r["workspace_bytes"]},
         "ns_tflops_whole_step": nominal / (ms_per_step * 1e-3) / 1e12,
         "ns_tflops_gemm_time": nominal * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None,
         "ns_pct_of_bf16_peak_whole_step": 100.0 * nominal / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -211,9 +236,20 @@ def main() -> int:
         "elementwise": ew,
         "roofline": roofline,
     }
-    st.close()
-    del tensors
-    torch.cuda.empty_cache()
+    if not args.no_others:
+        # The other single-GPU workloads of the target, each through the same timed loop (fewer steps); the headline
+        # fields above stay those of --config.
+        out["other_workloads"] = []
+        for other in OTHER_WORKLOADS:
+            if other == args.config:
+                continue
+            o = time_workload(other, max(2, args.steps // 2), 2, args.max_workspace_gib, dev)
+            out["other_workloads"].append({
+                "workload": other, "ms_per_step": o["ms_per_step"], "steps_per_s": 1e3 / o["ms_per_step"],
+                "ns_gemm_tflops_nominal": o["roofline"]["achieved"], "frac_of_bf16_peak": o["roofline"]["frac"],
+                "ns_gemm_tflops_executed": o["roofline"]["executed_tflops"],
+                "avg_gemm_launch_ms": o["roofline"]["avg_launch_ms"], "launches_per_step": o["roofline"]["launches_per_step"],
+                "elementwise": o["elementwise"]})
     out["adamw_non_matrix_params"] = bench_adamw(dev)
     torch.cuda.empty_cache()
     if bf16:
