@@ -123,3 +123,25 @@ def test_product_package_does_not_touch_the_oracle():
     for line in bench.splitlines():
         if "oracle" in line and "import" in line:
             assert "cpu_baseline" in bench
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message and a non-zero status before touching any device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    proc = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                          timeout=120)
+    assert proc.returncode != 0
+    assert "one GPU" in proc.stderr
+    assert proc.stdout.strip() == ""
+
+
+def test_schedule_helper_builds_a_host_array(binding):
+    hp = binding.default_hparams(coeff_schedule=[(1.0, 2.0, 3.0), (4.0, 5.0, 6.0)])
+    assert hp.ns_steps == 2
+    assert [hp.coeff_schedule[i] for i in range(6)] == [1.0, 2.0, 3.0, 4.0, 5.0, 6.0]
+    binding.set_coeff_schedule(hp, None)
+    assert not hp.coeff_schedule
+    with pytest.raises(ValueError):
+        binding.default_hparams(coeff_schedule=[(1.0, 2.0)])
