@@ -94,7 +94,8 @@ __device__ long long g_dbg_clk[8192 * 2];
 template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB>
 __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const GemmProblem* __restrict__ probs,
                                                                             const GemmTile* __restrict__ tiles,
-                                                                            float beta_acc, float beta_e, int alpha_idx) {
+                                                                            float beta_acc, float beta_e, int alpha_idx,
+                                                                            float diag_add) {
   constexpr int NW = WM_ * WN_, NT = NW * 64;
   constexpr int WTM = BM / WM_, WTN = BN / WN_;    // wave tile
   constexpr int FM = WTM / 32, FN = WTN / 32;      // 32x32 MFMA tiles per wave
@@ -338,6 +339,9 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   // wm*WTM/8 + 4i + q, half h.  The swizzle key c % CPT equals r % CPT, so the slot address is a per-lane base
   // XOR a compile-time constant.  The addend pieces of tile t+1 are read while tile t is being combined.
   u32x2 pk[FM][FN][4];
+  // diagonal constant: only MFMA tiles i == j of the waves on the tile's diagonal (wm == wn) of a diagonal tile
+  // hold elements C[r][r]; within such an MFMA tile, row 8q + 4h + e meets column fr
+  const bool diag_here = p.diag_add != 0 && tile.ti == tile.tj && wm == wn;
   const unsigned slot_base = (unsigned)((wn * WTN + fr) * (BM * 2) + fh * 8) + ((unsigned)((wm * (WTM / 8)) ^ (fr & (CPT - 1))) << 4);
   auto slot_of = [&](int i, int j, int q) -> unsigned char* {
     return smem + ((slot_base + (unsigned)(j * 32 * BM * 2)) ^ (unsigned)((4 * i + q) << 4));
@@ -368,6 +372,12 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
           x[1] = fmaf(ab_e, __uint_as_float(e2.x & 0xffff0000u), x[1]);
           x[2] = fmaf(ab_e, __uint_as_float(e2.y << 16), x[2]);
           x[3] = fmaf(ab_e, __uint_as_float(e2.y & 0xffff0000u), x[3]);
+        }
+        if (i == j && BM == BN && FM == FN) {
+          if (diag_here) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] += (fr == 8 * q + 4 * fh + e) ? diag_add : 0.f;
+          }
         }
         const f32x2 lo = {x[0], x[1]}, hi = {x[2], x[3]};
         pk[i][j][q].x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
@@ -499,12 +509,12 @@ hipError_t gemm_setup() {
 }
 
 hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
-                            float beta_e, int alpha_idx, hipStream_t s) {
+                            float beta_e, int alpha_idx, float diag_add, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
   if (shape == kShape128)
-    GEMM_S128<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx);
+    GEMM_S128<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
   else if (shape == kShape256)
-    GEMM_S256<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx);
+    GEMM_S256<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -73,6 +73,10 @@ constexpr int kCoarse = 256;   // block tile of the large bf16 kernel
 
 // The bf16 kernel's cheap output is the transposed one: a last iteration that needs only X is posed swapped.
 bool swapped_last(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16 && !q.transposed; }
+// bf16 path, m >= 64: the a*X term of Eq. 2 is folded into the polynomial, B' = b A + c A A + a I, so that the apply
+// product X' = B' X needs no addend (a third of its epilogue's memory traffic).  B's diagonal is rounded to bf16
+// once either way; for tiny matrices, where the diagonal carries most of the product, the explicit addend is kept.
+bool folds_identity(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16 && q.m >= 64; }
 
 // Workgroups are handed to the 8 accelerator dies (XCDs, each with a private L2) round-robin by workgroup index:
 // entry b of a tile table runs on XCD b % 8.  Tiles that share operand panels are therefore dealt to the same
@@ -437,7 +441,9 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         // polynomial: B = b A + c A A  (A is symmetric, so it is its own transposed addend)
         gp.L = d.Ag; gp.R = d.Ag; gp.E = d.Ag; gp.Et = d.Ag; gp.C = d.Bp; gp.Ct = nullptr;
         gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.mp; gp.ldet = q.mp; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+        gp.diag_add = folds_identity(q, ns_dtype) ? 1 : 0;
         reinterpret_cast<GemmProblem*>(img.data() + g.prob_poly)[k] = gp;
+        gp.diag_add = 0;
         // apply: X' = a X + B X, reading X^T from Xt[p], writing X in place and X'^T to Xt[p^1].
         // The last iteration writes only the layout W needs; when that is X itself, the bf16 kernel gets the
         // product posed the other way round (X'^T = X^T B, output through its transposed store).
@@ -456,6 +462,7 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
                 gp.Ct = nullptr;
               }
             }
+            if (folds_identity(q, ns_dtype)) { gp.E = nullptr; gp.Et = nullptr; }
             reinterpret_cast<GemmProblem*>(img.data() + g.prob_apply[par * 2 + last])[k] = gp;
           }
       }
@@ -578,7 +585,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           if (ts.n_sym == 0) continue;
           if (bf)
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f,
-                                                        first ? 1 : -1, s));
+                                                        first ? 1 : -1, 0.f, s));
           else
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f, first ? 1 : -1, s));
         }
@@ -586,7 +593,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
           if (bf)
-            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, s));
           else
             MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
         }
@@ -597,7 +604,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           if (n_app == 0) continue;
           if (bf)
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_apply[par * 2 + last]), T(t_app),
-                                                              n_app, 1.f, a, first ? 0 : -1, s));
+                                                              n_app, 1.f, a, first ? 0 : -1, 0.f, s));
           else
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(t_app), n_app, 1.f, a,
                                                              first ? 0 : -1, s));

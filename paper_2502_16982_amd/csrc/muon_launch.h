@@ -21,9 +21,10 @@ hipError_t launch_momentum_norm_cast(const MatDesc* mats, const MatPtrs* ptrs, c
 // a2 second stage: fixed-order sum of the partials of each matrix, s = 1/(sqrt(sum)+eps).
 hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, double eps, hipStream_t s);
 
-// a4-a6: grouped NT GEMM with fused epilogue.  alpha_idx: -1 none, 0 -> scal[0], 1 -> scal[1].
+// a4-a6: grouped NT GEMM with fused epilogue.  alpha_idx: -1 none, 0 -> scal[0], 1 -> scal[1].  diag_add: constant
+// added to the diagonal of the outputs of problems that ask for it (GemmProblem::diag_add), bf16 kernel only.
 hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
-                            float beta_acc, float beta_e, int alpha_idx, hipStream_t s);
+                            float beta_acc, float beta_e, int alpha_idx, float diag_add, hipStream_t s);
 hipError_t launch_gemm_f32(const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
                            float beta_acc, float beta_e, int alpha_idx, hipStream_t s);
 

@@ -44,7 +44,8 @@ struct EwTile {
 };
 
 // One product  C[i][j] = sum_k L[i][k] * R[j][k]  ("NT": both operands contiguous along k),
-// followed by  val = alpha * (beta_acc * acc + beta_e * E[i][j])  and stores of C and/or its transpose.
+// followed by  val = alpha * (beta_acc * acc + beta_e * E[i][j]) (+ d on the matrix diagonal when diag_add is set;
+// d is a launch argument)  and stores of C and/or its transpose.
 // The bf16 kernel writes Ct straight from the accumulator layout and C through one extra MFMA transpose,
 // so single-output problems are posed with Ct as the output.
 struct GemmProblem {
@@ -58,6 +59,7 @@ struct GemmProblem {
   int32_t K;
   int32_t ldl, ldr, lde, ldet, ldc, ldct;
   int32_t symmetric;  // output is symmetric: off-diagonal tiles are also stored mirrored into C
+  int32_t diag_add;   // square output only: add the launch's diagonal constant to C[i][i] before rounding
 };
 
 struct GemmTile {
