@@ -142,11 +142,15 @@ def time_workload(name, steps, warmup, max_ws_gib, dev):
     torch.cuda.synchronize()
     binding.muon_profile_enable(st.ctx, True)
     binding.muon_profile_read(st.ctx, reset=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
-    for _ in range(steps):
+    marks[0].record(stream)
+    for i in range(steps):
         st.step(hp, stream=stream)
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     prof = binding.muon_profile_read(st.ctx, reset=True)
     binding.muon_profile_enable(st.ctx, False)
 
@@ -188,6 +192,7 @@ def time_workload(name, steps, warmup, max_ws_gib, dev):
     del tensors
     torch.cuda.empty_cache()
     return {"wl": wl, "hyper": h, "bf16": bf16, "elapsed": elapsed, "ms_per_step": ms_per_step, "nominal": nominal,
+            "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
             "executed": executed, "gemm_ms": gemm_ms, "prof": prof, "roofline": roofline, "elementwise": ew, "n_el": n_el,
             "chunks": chunks, "workspace_bytes": ws_bytes}
 
@@ -222,6 +227,7 @@ def main() -> int:
     out = {
         "metric": "muon_steps_per_sec", "value": args.steps / elapsed, "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "matrices": len(wl.shapes), "elements": n_el,
@@ -246,6 +252,7 @@ def main() -> int:
             o = time_workload(other, max(2, args.steps // 2), 2, args.max_workspace_gib, dev)
             out["other_workloads"].append({
                 "workload": other, "ms_per_step": o["ms_per_step"], "steps_per_s": 1e3 / o["ms_per_step"],
+                "ms_per_step_median": o["ms_per_step_median"], "ms_per_step_min": o["ms_per_step_min"],
                 "ns_gemm_tflops_nominal": o["roofline"]["achieved"], "frac_of_bf16_peak": o["roofline"]["frac"],
                 "ns_gemm_tflops_executed": o["roofline"]["executed_tflops"],
                 "avg_gemm_launch_ms": o["roofline"]["avg_launch_ms"], "launches_per_step": o["roofline"]["launches_per_step"],
