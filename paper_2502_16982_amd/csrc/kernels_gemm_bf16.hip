@@ -42,6 +42,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef const __attribute__((address_space(1))) void* gptr;
 typedef __attribute__((address_space(3))) void* lptr;
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16* lds_v4i16_ptr;
 typedef __attribute__((address_space(1))) u32x4* gvec_ptr;   // 16-byte global store target (keeps the stores off the flat path)
 
 constexpr int BK = 64;        // K slab in elements: one 128-byte line per row, the request size the L1 serves at full rate
@@ -91,7 +93,9 @@ __device__ long long g_dbg_clk[8192 * 2];
 #define DBG_E(slot) do {} while (0)
 #endif
 
-template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB>
+// LKM: the L operand is stored K-major (element (i, k) at L[k * ldl + i], i.e. the product is L^T-by-R^T of two
+// row-major arrays); its MFMA fragments then come from LDS through the transposing read ds_read_b64_tr_b16.
+template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB, bool LKM>
 __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const GemmProblem* __restrict__ probs,
                                                                             const GemmTile* __restrict__ tiles,
                                                                             float beta_acc, float beta_e, int alpha_idx,
@@ -126,9 +130,16 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   const int dma_row = wave * 8 + (lane >> 3);
   const int dma_key = ((lane >> 4) & 3) + 4 * (wave & 1);
   const int dma_chunk = (lane & 7) ^ dma_key;
-  const u16* lsrc = static_cast<const u16*>(p.L) + (size_t)(row0 + dma_row) * p.ldl + dma_chunk * 8;
+  // K-major L: a slab is 64 k-rows of BM elements; a wave instruction fills RPK whole k-rows; position s of k-row
+  // R holds logical chunk s ^ 4*(R%4), which spreads the four k-rows a transposing read touches over the banks.
+  constexpr int CPRK = BM / 8, RPK = 64 / CPRK;
+  const int km_row = wave * RPK + lane / CPRK;
+  const int km_chunk = (lane % CPRK) ^ (4 * (km_row & 3));
+  const u16* lsrc = LKM ? static_cast<const u16*>(p.L) + (size_t)km_row * p.ldl + row0 + km_chunk * 8
+                        : static_cast<const u16*>(p.L) + (size_t)(row0 + dma_row) * p.ldl + dma_chunk * 8;
   const u16* rsrc = static_cast<const u16*>(p.R) + (size_t)(col0 + dma_row) * p.ldr + dma_chunk * 8;
-  const size_t lstep = (size_t)(8 * NW) * p.ldl, rstep = (size_t)(8 * NW) * p.ldr;
+  const size_t lstep = (size_t)(LKM ? NW * RPK : 8 * NW) * p.ldl, rstep = (size_t)(8 * NW) * p.ldr;
+  const size_t lslab = LKM ? (size_t)BK * p.ldl : (size_t)BK;      // elements from one K slab of L to the next
   // requests DMA instructions [first, first + count) of slab kt (instructions 0..LI-1 fetch L rows, the rest R rows)
   auto request_part = [&](int kt, int stage, auto first_tag, auto count_tag) {
     constexpr int FIRST = decltype(first_tag)::value, COUNT = decltype(count_tag)::value;
@@ -136,7 +147,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
     for (int n = FIRST; n < FIRST + COUNT; ++n) {
       if (n < LI)
-        __builtin_amdgcn_global_load_lds((gptr)(lsrc + n * lstep + (size_t)kt * BK), (lptr)(base + n * NW * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr)(lsrc + n * lstep + (size_t)kt * lslab), (lptr)(base + n * NW * 1024), 16, 0, 0);
       else
         __builtin_amdgcn_global_load_lds((gptr)(rsrc + (n - LI) * rstep + (size_t)kt * BK),
                                          (lptr)(base + BM * ROWB + (n - LI) * NW * 1024), 16, 0, 0);
@@ -165,11 +176,23 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+  // K-major L: the 16 lanes of a group (g = lane/16) each address 8 bytes of a 4 (k) x 16 (i) block - lane l: k-row
+  // l/4, columns 4*(l%4)..+3 - and each receives one column's 4 consecutive k values; two such reads make the 8
+  // k values (8h..8h+7, h = g/2) that lane r = lane%32 owes the MFMA for row i = 32*tile + r.
+  int a_km[FM];
+  {
+    const int l16 = lane & 15, g = lane >> 4, r4 = l16 >> 2;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+      a_km[i] = (8 * (g >> 1) + r4) * (BM * 2) + ((((wm * (WTM / 8) + 4 * i) ^ (4 * r4)) + 2 * (g & 1) + ((l16 & 3) >> 1)) * 16) + (l16 & 1) * 8;
+  }
   bf16x8 af[KSTEPS][FM], bfr[KSTEPS][FN];
   auto fread = [&](int stage, int kk) {
     const unsigned char* s = smem + stage * STAGE_B + (((2 * kk + fh) ^ fkey) * 16);
+    {
 #pragma unroll
-    for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(s + a_base + i * 32 * ROWB);
+      for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(s + a_base + i * 32 * ROWB);
+    }
 #pragma unroll
     for (int j = 0; j < FN; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(s + b_base + j * 32 * ROWB);
   };
@@ -179,6 +202,40 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
       for (int j = 0; j < FN; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[i][j], 0, 0, 0);
+  };
+  // K-major path: the assembly reads take no part in the compiler's instruction-group scheduling, so phases A and
+  // B are written out instruction by instruction (read number r of k-step kk: the A-side tile rows first - two
+  // transposing reads each - then the B-side tiles; MFMA number t of a k-step: tile (t / FN, t % FN)).
+  constexpr int RPS = 2 * FM + FN;               // LDS read instructions per k-step on the K-major path
+  // On this path ALL fragment reads are assembly and the waits for them are placed by hand (the compiler neither
+  // sees the reads nor counts them): one wait for the k-step-0 fragments before phase B's first MFMA, one for
+  // everything at the end of phase B.  The LDS returns data in issue order.
+  u32x2 km_half[KSTEPS][FM][2];
+  u32x4 km_b[KSTEPS][FN];
+  auto read_one = [&](int stage, int kk, int r) {
+    if (r < 2 * FM) {
+      const int i = r >> 1, half = r & 1;
+      const unsigned addr = (unsigned)(size_t)(lds_v4i16_ptr)(smem + stage * STAGE_B + (16 * kk) * (BM * 2) + a_km[i]);
+      if (half == 0) asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(km_half[kk][i][0]) : "v"(addr) : "memory");
+      else asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(km_half[kk][i][1]) : "v"(addr), "n"(4 * (BM * 2)) : "memory");
+    } else {
+      const int j = r - 2 * FM;
+      const unsigned addr = (unsigned)(size_t)(lds_v4i16_ptr)(smem + stage * STAGE_B + (((2 * kk + fh) ^ fkey) * 16) + b_base + j * 32 * ROWB);
+      asm volatile("ds_read_b128 %0, %1" : "=v"(km_b[kk][j]) : "v"(addr) : "memory");
+    }
+  };
+  auto mma_one = [&](int kk, int t) {
+    const int i = t / FN, j = t % FN;
+    bf16x8 a, b;
+    if (LKM) {
+      const u32x4 both = {km_half[kk][i][0].x, km_half[kk][i][0].y, km_half[kk][i][1].x, km_half[kk][i][1].y};
+      a = __builtin_bit_cast(bf16x8, both);
+      b = __builtin_bit_cast(bf16x8, km_b[kk][j]);
+    } else {
+      a = af[kk][i];
+      b = bfr[kk][j];
+    }
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
   };
   // ---- pipeline: two LDS stages.  A wave instruction that requests 1 KB keeps the wave's (in-order) issue port
   // busy until the memory pipeline accepts it - measured ~57 clocks each when 4 waves request 16 KB apiece in a
@@ -198,6 +255,10 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int t = 0; t < 8; ++t) af[KSTEPS - 1][i][t] = (__bf16)0.0f;     // first pass of phase A multiplies zeros
+#pragma unroll
+  for (int i = 0; i < FM; ++i) km_half[KSTEPS - 1][i][0] = km_half[KSTEPS - 1][i][1] = u32x2{0u, 0u};
+#pragma unroll
+  for (int j = 0; j < FN; ++j) km_b[KSTEPS - 1][j] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
   for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -231,7 +292,41 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   // must be visible afterwards)
   auto iteration = [&](auto refill_tag, auto sync_tag) {
     constexpr bool REFILL = decltype(refill_tag)::value, SYNC = decltype(sync_tag)::value;
+    constexpr int DSG = 2 * ((LKM ? 2 : 1) * FM + FN) / (FM + FN);   // LDS reads per scheduling group of phases A, B
     DBG_T(0);
+    if (LKM) {
+      constexpr int NG = FM + FN, RG = 2 * RPS / NG, MT = FM * FN;
+      constexpr int LEAD = MT >= NG + 2 ? 2 : 0; // MFMAs of k-step 0 issued ahead of phase B's reads
+      static_assert(!LKM || (2 * RPS % NG == 0 && MT % NG == 0 && MT >= NG + LEAD), "K-major phase layout");
+      // A: reads of k-steps 0, 1 under the MFMAs of k-step 3 of the previous slab
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r) read_one(cur, (g * RG + r) / RPS, (g * RG + r) % RPS);
+#pragma unroll
+        for (int t = 0; t < MT / NG; ++t) mma_one(KSTEPS - 1, g * (MT / NG) + t);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      DBG_T(1);
+      // B: MFMAs of k-step 0 lead, then one per group of reads of k-steps 2, 3
+      __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | ((RPS < 15 ? RPS : 15) << 8));   // lgkmcnt(RPS): k-step 0 is in
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int t = 0; t < LEAD; ++t) mma_one(0, t);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r) read_one(cur, 2 + (g * RG + r) / RPS, (g * RG + r) % RPS);
+        mma_one(0, LEAD + g);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int t = LEAD + NG; t < MT; ++t) mma_one(0, t);
+      __builtin_amdgcn_sched_barrier(0);
+      wait_lgkm0();                              // k-steps 1..3 are in (and nobody of this wave reads the stage any more)
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
     // A
     fread(cur, 0);
     fread(cur, 1);
@@ -239,7 +334,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     mma(KSTEPS - 1);
 #pragma unroll
     for (int g = 0; g < FM + FN; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, DSG, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);
       if (SYNC && TAIL > 0 && g % ((FM + FN) / (TAIL > 0 ? TAIL : 1)) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
@@ -254,12 +349,13 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 #pragma unroll
     for (int g = 0; g < FM + FN; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, DSG, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if (SYNC && TAIL > 0 && g % ((FM + FN) / (TAIL > 0 ? TAIL : 1)) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);
     __builtin_amdgcn_sched_barrier(0);
+    }
     DBG_T(2);
     if (REFILL) {
       wait_lgkm0();                              // my fragment reads have returned
@@ -270,7 +366,14 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     // C
     if (!REFILL && !SYNC && Et) et_request(cur ^ 1);
 #pragma unroll
-    for (int kk = 1; kk < KSTEPS - 1; ++kk) mma(kk);
+    for (int kk = 1; kk < KSTEPS - 1; ++kk) {
+      if (LKM) {
+#pragma unroll
+        for (int t = 0; t < FM * FN; ++t) mma_one(kk, t);
+      } else {
+        mma(kk);
+      }
+    }
     if (!REFILL && !SYNC) {
 #pragma unroll
       for (int g = 0; g < 8; ++g) {
@@ -300,7 +403,12 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   while (kt + 2 < KT) iteration(T_{}, T_{});
   if (kt + 1 < KT) iteration(F_{}, T_{});
   iteration(F_{}, F_{});
-  mma(KSTEPS - 1);                               // k-step 3 of the last slab
+  if (LKM) {                                     // k-step 3 of the last slab
+#pragma unroll
+    for (int t = 0; t < FM * FN; ++t) mma_one(KSTEPS - 1, t);
+  } else {
+    mma(KSTEPS - 1);
+  }
   DBG_BLK(1);
 #ifdef MUON_DBG_TIMING
   if (tid == 0 && blockIdx.x < 8192) g_dbg_clk[blockIdx.x * 2 + 1] = clock64();
@@ -390,7 +498,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   if (Et) combine(std::true_type{}); else combine(std::false_type{});
 
   DBG_E(4);
-  {
+  if (Ct) {
     __syncthreads();
     DBG_E(5);
     constexpr int SB = TI < 8 ? TI : 8;          // image chunks read per batch before they are stored
@@ -487,12 +595,15 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 }
 
 // ---- instantiations: {tile, waves, stages, waves per SIMD} per GemmShape ----
-#define GEMM_S128 ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2>
+#define GEMM_S128 ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, false>
+#define GEMM_S128K ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, true>
 #ifdef MUON_GEMM_256_W8
-#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 4, 2, 2>
+#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 4, 2, 2, false>
+#define GEMM_S256K ns_gemm_bf16_kernel<256, 256, 2, 4, 2, 2, true>
 #define GEMM_S256_THREADS 512
 #else
-#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1>
+#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, false>
+#define GEMM_S256K ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, true>
 #define GEMM_S256_THREADS 256
 #endif
 constexpr size_t kLds128 = TileCfg<128, 128>::lds_bytes(2);
@@ -501,22 +612,31 @@ constexpr size_t kLds256 = TileCfg<256, 256>::lds_bytes(2);
 }  // namespace
 
 hipError_t gemm_setup() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&GEMM_S128), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     (int)kLds128);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&GEMM_S256), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)kLds256);
+  const void* k128[] = {reinterpret_cast<const void*>(&GEMM_S128), reinterpret_cast<const void*>(&GEMM_S128K)};
+  const void* k256[] = {reinterpret_cast<const void*>(&GEMM_S256), reinterpret_cast<const void*>(&GEMM_S256K)};
+  for (const void* f : k128) {
+    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds128);
+    if (e != hipSuccess) return e;
+  }
+  for (const void* f : k256) {
+    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds256);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
-                            float beta_e, int alpha_idx, float diag_add, hipStream_t s) {
+                            float beta_e, int alpha_idx, float diag_add, int l_kmajor, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
-  if (shape == kShape128)
-    GEMM_S128<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
-  else if (shape == kShape256)
-    GEMM_S256<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
-  else
+  if (shape == kShape128) {
+    if (l_kmajor) GEMM_S128K<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+    else GEMM_S128<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+  } else if (shape == kShape256) {
+    if (l_kmajor) GEMM_S256K<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+    else GEMM_S256<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+  } else {
     return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -585,7 +585,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           if (ts.n_sym == 0) continue;
           if (bf)
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f,
-                                                        first ? 1 : -1, 0.f, s));
+                                                        first ? 1 : -1, 0.f, 0, s));
           else
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f, first ? 1 : -1, s));
         }
@@ -593,7 +593,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
           if (bf)
-            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, s));
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, 0, s));
           else
             MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
         }
@@ -604,7 +604,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           if (n_app == 0) continue;
           if (bf)
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_apply[par * 2 + last]), T(t_app),
-                                                              n_app, 1.f, a, first ? 0 : -1, 0.f, s));
+                                                              n_app, 1.f, a, first ? 0 : -1, 0.f, 0, s));
           else
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(t_app), n_app, 1.f, a,
                                                              first ? 0 : -1, s));
