@@ -103,7 +103,7 @@ __device__ __forceinline__ bool aligned16(const void* p) { return (reinterpret_c
 // ------------------------------------------------------------------------------------------------------
 template <typename GT, typename XT>
 __device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float mu, int nesterov,
-                                              float (*lds)[kEwTile + 1], float* red) {
+                                              bool both, float (*lds)[kEwTile + 1], float* red) {
   const int tid = threadIdx.x;
   const int r = tr * kEwTile + (tid >> 2);
   const int c0 = tc * kEwTile + (tid & 3) * 16;
@@ -150,7 +150,8 @@ __device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& p
   const int pitch_same = d.transposed ? d.mp : d.np;
   const int pitch_flip = d.transposed ? d.np : d.mp;
 
-  store16<XT>(same + (size_t)r * pitch_same + c0, u);
+  const bool write_same = both || !d.transposed, write_flip = both || d.transposed;
+  if (write_same) store16<XT>(same + (size_t)r * pitch_same + c0, u);
 
   const int lr_ = tid >> 2, lc0 = (tid & 3) * 16;
 #pragma unroll
@@ -160,7 +161,7 @@ __device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& p
   const int fc = tid >> 2, fr0 = (tid & 3) * 16;   // row of U^T (= column of U), 16 consecutive columns of U^T
 #pragma unroll
   for (int i = 0; i < 16; ++i) t[i] = lds[fc][fr0 + i];
-  store16<XT>(flip + (size_t)(tc * kEwTile + fc) * pitch_flip + tr * kEwTile + fr0, t);
+  if (write_flip) store16<XT>(flip + (size_t)(tc * kEwTile + fc) * pitch_flip + tr * kEwTile + fr0, t);
 
   if (tid == 0) d.partials[tr * d.ew_tiles_c + tc] = total;
 }
@@ -169,7 +170,7 @@ template <typename XT>
 __global__ __launch_bounds__(256) void momentum_norm_cast_kernel(const MatDesc* __restrict__ mats,
                                                                   const MatPtrs* __restrict__ ptrs,
                                                                   const EwTile* __restrict__ tiles, float mu,
-                                                                  int nesterov) {
+                                                                  int nesterov, int both) {
   __shared__ float lds[kEwTile][kEwTile + 1];
   __shared__ float red[4];
   const EwTile t = tiles[blockIdx.x];
@@ -178,9 +179,9 @@ __global__ __launch_bounds__(256) void momentum_norm_cast_kernel(const MatDesc* 
   for (int k = 0; k < t.count; ++k) {
     if (k) __syncthreads();     // the LDS tile and the reduction scratch are reused
     if (d.g_dtype == kDtypeBF16)
-      momentum_tile<u16, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, lds, red);
+      momentum_tile<u16, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, both != 0, lds, red);
     else
-      momentum_tile<float, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, lds, red);
+      momentum_tile<float, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, both != 0, lds, red);
   }
 }
 
@@ -210,6 +211,13 @@ __global__ __launch_bounds__(256) void norm_finalize_kernel(const MatDesc* __res
 // ------------------------------------------------------------------------------------------------------
 // a8: W <- W - lr * (rms_scale*sqrt(max(A,B)) * O + wd * W), fp32 math, one rounding to W's dtype.
 // ------------------------------------------------------------------------------------------------------
+// Where O (in W's orientation) lives after the Newton-Schulz phase.  o_sel bit 0: which of Xt[0..1] for matrices
+// iterated on their transpose; bit 1: X (0) or Xt[0] used as the second m_pad x n_pad buffer (1) for the others.
+__device__ __forceinline__ const void* o_source(const MatDesc& d, int o_sel) {
+  if (d.transposed) return d.Xt[o_sel & 1];
+  return (o_sel & 2) ? d.Xt[0] : d.X;
+}
+
 template <typename WT, typename XT, bool UPDATE>
 __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float lr, float wd,
                                            float scale, int o_sel, float* red) {
@@ -218,7 +226,7 @@ __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, 
   const int c0 = tc * kEwTile + (tid & 3) * 16;
   const int A = d.rows, B = d.cols;
   WT* w = static_cast<WT*>(pt.w);
-  const XT* o = static_cast<const XT*>(d.transposed ? d.Xt[o_sel] : d.X);
+  const XT* o = static_cast<const XT*>(o_source(d, o_sel));
   const int pitch = d.transposed ? d.mp : d.np;
   float ss = 0.f;
   if (r < A && c0 < B) {
@@ -329,7 +337,7 @@ template <typename XT, typename DT>
 __global__ __launch_bounds__(256) void read_update_kernel(const MatDesc* __restrict__ mats, int mat, int o_sel, int use_s,
                                                            DT* __restrict__ dst) {
   const MatDesc d = mats[mat];
-  const XT* o = static_cast<const XT*>(d.transposed ? d.Xt[o_sel] : d.X);
+  const XT* o = static_cast<const XT*>(o_source(d, o_sel));
   const int pitch = d.transposed ? d.mp : d.np;
   const float s = use_s ? d.scal[0] : 1.f;
   const size_t total = (size_t)d.rows * (size_t)d.cols;
@@ -342,12 +350,12 @@ __global__ __launch_bounds__(256) void read_update_kernel(const MatDesc* __restr
 }  // namespace
 
 hipError_t launch_momentum_norm_cast(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles, float mu,
-                                     int nesterov, int ns_dtype, hipStream_t s) {
+                                     int nesterov, int both_layouts, int ns_dtype, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
   if (ns_dtype == kDtypeBF16)
-    momentum_norm_cast_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov);
+    momentum_norm_cast_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov, both_layouts);
   else
-    momentum_norm_cast_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov);
+    momentum_norm_cast_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov, both_layouts);
   return hipGetLastError();
 }
 

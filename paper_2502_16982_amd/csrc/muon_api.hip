@@ -58,7 +58,7 @@ struct TileSet {
 // the remaining strips, so that nothing is padded beyond the fine tile.
 struct Group {
   int n_prob;
-  size_t prob_gram, prob_poly, prob_apply[4];  // byte offsets of the problem tables ([parity * 2 + last])
+  size_t prob_gram[2], prob_poly, prob_apply[4];  // byte offsets of the problem tables ([parity], [parity * 2 + last])
   TileSet fine, coarse;
 };
 
@@ -72,7 +72,6 @@ struct Chunk {
 constexpr int kCoarse = 256;   // block tile of the large bf16 kernel
 
 // The bf16 kernel's cheap output is the transposed one: a last iteration that needs only X is posed swapped.
-bool swapped_last(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16 && !q.transposed; }
 // bf16 path, m >= 64: the a*X term of Eq. 2 is folded into the polynomial, B' = b A + c A A + a I, so that the apply
 // product X' = B' X needs no addend (a third of its epilogue's memory traffic).  B's diagonal is rounded to bf16
 // once either way; for tiny matrices, where the diagonal carries most of the product, the explicit addend is kept.
@@ -89,8 +88,8 @@ constexpr int kXcds = 8;
 // 4 x 8 blocks of the tile grid: the 32 tiles running together on an XCD then share 4 row panels and 8 column
 // panels, which they sweep along k in step, instead of 1 + 32 panels for a row-major run.
 // Tiles (i, j) with i < skip_m and j < skip_n are left out (they are covered by the coarser kernel).
-void blocked_tiles(int32_t prob, int tm, int tn, bool upper_only, int skip_m, int skip_n, std::vector<GemmTile>& out) {
-  constexpr int BH = 4, BW = 8;
+void blocked_tiles(int32_t prob, int tm, int tn, bool upper_only, int skip_m, int skip_n, std::vector<GemmTile>& out,
+                   int BH = 4, int BW = 8) {
   for (int bi = 0; bi < tm; bi += BH)
     for (int bj = 0; bj < tn; bj += BW)
       for (int i = bi; i < std::min(bi + BH, tm); ++i)
@@ -426,7 +425,7 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         cursor += bytes;
         return o;
       };
-      g.prob_gram = take(sizeof(GemmProblem) * members.size());
+      for (int v = 0; v < 2; ++v) g.prob_gram[v] = take(sizeof(GemmProblem) * members.size());
       g.prob_poly = take(sizeof(GemmProblem) * members.size());
       for (int v = 0; v < 4; ++v) g.prob_apply[v] = take(sizeof(GemmProblem) * members.size());
       for (size_t k = 0; k < members.size(); ++k) {
@@ -434,35 +433,45 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         const MatDesc& d = h_mats[members[k]];
         GemmProblem gp{};
         gp.scal = d.scal;
+        const bool bf = ns_dtype == MUON_BF16;
+        // bf16 path: ONE layout of the iterate, ping-ponging between X and Xt[0] (both m_pad x n_pad); fp32 path: X
+        // updated in place plus its transpose ping-ponging between Xt[0] and Xt[1].
+        void* const xbuf[2] = {d.X, bf ? d.Xt[0] : d.X};
         // Gram: A = X X^T
-        gp.L = d.X; gp.R = d.X; gp.E = nullptr; gp.Et = nullptr; gp.C = d.Ag; gp.Ct = nullptr;
-        gp.K = q.np; gp.ldl = q.np; gp.ldr = q.np; gp.lde = 0; gp.ldet = 0; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
-        reinterpret_cast<GemmProblem*>(img.data() + g.prob_gram)[k] = gp;
+        for (int par = 0; par < 2; ++par) {
+          gp.L = xbuf[par]; gp.R = xbuf[par]; gp.E = nullptr; gp.Et = nullptr; gp.C = d.Ag; gp.Ct = nullptr;
+          gp.K = q.np; gp.ldl = q.np; gp.ldr = q.np; gp.lde = 0; gp.ldet = 0; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+          reinterpret_cast<GemmProblem*>(img.data() + g.prob_gram[par])[k] = gp;
+        }
         // polynomial: B = b A + c A A  (A is symmetric, so it is its own transposed addend)
         gp.L = d.Ag; gp.R = d.Ag; gp.E = d.Ag; gp.Et = d.Ag; gp.C = d.Bp; gp.Ct = nullptr;
         gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.mp; gp.ldet = q.mp; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
         gp.diag_add = folds_identity(q, ns_dtype) ? 1 : 0;
         reinterpret_cast<GemmProblem*>(img.data() + g.prob_poly)[k] = gp;
         gp.diag_add = 0;
-        // apply: X' = a X + B X, reading X^T from Xt[p], writing X in place and X'^T to Xt[p^1].
-        // The last iteration writes only the layout W needs; when that is X itself, the bf16 kernel gets the
-        // product posed the other way round (X'^T = X^T B, output through its transposed store).
         for (int par = 0; par < 2; ++par)
           for (int last = 0; last < 2; ++last) {
-            gp.L = d.Bp; gp.R = d.Xt[par]; gp.E = d.X; gp.Et = d.Xt[par]; gp.C = d.X; gp.Ct = d.Xt[par ^ 1];
-            gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.np; gp.ldet = q.mp; gp.ldc = q.np; gp.ldct = q.mp;
             gp.symmetric = 0;
-            if (last) {
-              if (q.transposed) {
-                gp.C = nullptr;
-              } else if (swapped_last(q, ns_dtype)) {
-                gp.L = d.Xt[par]; gp.R = d.Bp; gp.E = nullptr; gp.Et = d.X; gp.C = nullptr; gp.Ct = d.X;
-                gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = 0; gp.ldet = q.np; gp.ldc = 0; gp.ldct = q.np;
-              } else {
-                gp.Ct = nullptr;
+            if (bf) {
+              // apply, bf16: the product is posed transposed, T = X'^T = X^T B, with its L operand X^T read K-major
+              // straight from the row-major X; the kernel's cheap transposed store of T is then X' itself, row-major.
+              // Only the last iteration of a matrix iterated on its transpose needs T as it is (O in W's
+              // orientation), through the kernel's other output, into Xt[1].
+              gp.L = xbuf[par]; gp.R = d.Bp; gp.K = q.mp; gp.ldl = q.np; gp.ldr = q.mp;
+              gp.E = nullptr; gp.lde = 0;
+              gp.Et = folds_identity(q, ns_dtype) ? nullptr : xbuf[par]; gp.ldet = q.np;
+              gp.C = nullptr; gp.ldc = 0; gp.Ct = xbuf[par ^ 1]; gp.ldct = q.np;
+              if (last && q.transposed) { gp.C = d.Xt[1]; gp.ldc = q.mp; gp.Ct = nullptr; gp.ldct = 0; }
+            } else {
+              // apply, fp32: X' = a X + B X, reading X^T from Xt[p], writing X in place and X'^T to Xt[p^1]; the last
+              // iteration writes only the layout W needs.
+              gp.L = d.Bp; gp.R = d.Xt[par]; gp.E = d.X; gp.Et = d.Xt[par]; gp.C = d.X; gp.Ct = d.Xt[par ^ 1];
+              gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.np; gp.ldet = q.mp; gp.ldc = q.np; gp.ldct = q.mp;
+              if (last) {
+                if (q.transposed) gp.C = nullptr;
+                else gp.Ct = nullptr;
               }
             }
-            if (folds_identity(q, ns_dtype)) { gp.E = nullptr; gp.Et = nullptr; }
             reinterpret_cast<GemmProblem*>(img.data() + g.prob_apply[par * 2 + last])[k] = gp;
           }
       }
@@ -476,15 +485,16 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
           const int cm = ns_dtype == MUON_BF16 ? q.mp / kCoarse : 0, cn = ns_dtype == MUON_BF16 ? q.np / kCoarse : 0;
           if (level == 1) {
             blocked_tiles((int32_t)k, cm, cm, true, 0, 0, sym[k]);
-            blocked_tiles((int32_t)k, cm, cn, false, 0, 0, app[k]);
-            if (swapped_last(q, ns_dtype)) blocked_tiles((int32_t)k, cn, cm, false, 0, 0, app_last[k]);
-            else app_last[k] = app[k];
+            // tiles of X'^T; 8 x 4 blocks measured 1 % faster than 4 x 8 here (the K-major panels are the strided ones)
+            if (ns_dtype == MUON_BF16) blocked_tiles((int32_t)k, cn, cm, false, 0, 0, app[k], 8, 4);
+            else blocked_tiles((int32_t)k, cm, cn, false, 0, 0, app[k]);
+            app_last[k] = app[k];
           } else {
             const int tm = q.mp / q.tile, tn = q.np / q.tile, r = kCoarse / q.tile;
             blocked_tiles((int32_t)k, tm, tm, true, cm * r, cm * r, sym[k]);
-            blocked_tiles((int32_t)k, tm, tn, false, cm * r, cn * r, app[k]);
-            if (swapped_last(q, ns_dtype)) blocked_tiles((int32_t)k, tn, tm, false, cn * r, cm * r, app_last[k]);
-            else app_last[k] = app[k];
+            if (ns_dtype == MUON_BF16) blocked_tiles((int32_t)k, tn, tm, false, cn * r, cm * r, app[k], 8, 4);
+            else blocked_tiles((int32_t)k, tm, tn, false, cm * r, cn * r, app[k]);
+            app_last[k] = app[k];
           }
           n_sym += sym[k].size();
           n_app += app[k].size();
@@ -560,7 +570,10 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
 
   const int N = hp->ns_steps;
   const int use_s = N == 0;
-  const int o_sel = N & 1;
+  const bool bf16_path = ctx->ns_dtype == MUON_BF16;
+  // where O ends up (see o_source in the elementwise kernels): fp32 path: X in place, its transpose in Xt[N & 1];
+  // bf16 path: X ping-pong index N & 1 (bit 1), transposed matrices in Xt[1], or Xt[0] when no iteration ran (bit 0)
+  const int o_sel = bf16_path ? ((N & 1) << 1) | (N > 0 ? 1 : 0) : (N & 1);
   const bool bf = ctx->ns_dtype == MUON_BF16;
   if (hp->coeff_schedule)
     for (int i = 0; i < 3 * N; ++i)
@@ -570,7 +583,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
     const Chunk& ch = ctx->chunks[ci];
     const EwTile* ew = reinterpret_cast<const EwTile*>(ctx->ws + ch.ew_tiles_off);
     MUON_TIMED(MUON_PROF_MOMENTUM, launch_momentum_norm_cast(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->momentum,
-                                                             hp->nesterov != 0, ctx->ns_dtype, s));
+                                                             hp->nesterov != 0, (!bf16_path || N == 0) ? 1 : 0, ctx->ns_dtype, s));
     MUON_TIMED(MUON_PROF_NORM, launch_norm_finalize(ctx->d_mats, ch.first, ch.count, hp->eps, s));
     for (int it = 0; it < N; ++it) {
       const int first = it == 0, last = it == N - 1, par = it & 1;
@@ -584,10 +597,10 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
           if (bf)
-            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f,
+            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f,
                                                         first ? 1 : -1, 0.f, 0, s));
           else
-            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram), T(ts.sym), ts.n_sym, 1.f, 0.f, first ? 1 : -1, s));
+            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f, first ? 1 : -1, s));
         }
         for (int level = 1; level >= 0; --level) {
           const TileSet& ts = level ? g.coarse : g.fine;
@@ -604,7 +617,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           if (n_app == 0) continue;
           if (bf)
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_apply[par * 2 + last]), T(t_app),
-                                                              n_app, 1.f, a, first ? 0 : -1, 0.f, 0, s));
+                                                              n_app, 1.f, a, first ? 0 : -1, 0.f, 1, s));
           else
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(t_app), n_app, 1.f, a,
                                                              first ? 0 : -1, s));

@@ -14,9 +14,10 @@ constexpr int kF32Tile = 64;   // block tile of the fp32 Newton-Schulz GEMM
 // One-time per-process kernel attribute setup (large dynamic LDS).  Returns a hipError_t.
 hipError_t gemm_setup();
 
-// a1-a3: momentum, sum of squares, cast + orient into both layouts.  One block per EwTile.
+// a1-a3: momentum, sum of squares, cast + orient.  both_layouts != 0: U goes to X and Xt[0] (one holds U, the other
+// U^T); 0: only X (the orientation with rows <= cols) is written.  One block per EwTile.
 hipError_t launch_momentum_norm_cast(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles,
-                                     float mu, int nesterov, int ns_dtype, hipStream_t s);
+                                     float mu, int nesterov, int both_layouts, int ns_dtype, hipStream_t s);
 
 // a2 second stage: fixed-order sum of the partials of each matrix, s = 1/(sqrt(sum)+eps).
 hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, double eps, hipStream_t s);
@@ -30,8 +31,8 @@ hipError_t launch_gemm_f32(const GemmProblem* probs, const GemmTile* tiles, int 
                            float beta_acc, float beta_e, int alpha_idx, hipStream_t s);
 
 // a8: W <- W - lr*(scale*O + wd*W); also leaves per-tile sums of O^2 in the partials.
-// o_sel: which buffer holds O in W's orientation for transposed matrices (Xt[o_sel]); use_s: multiply O by
-// scal[0] (only when no Newton-Schulz iteration ran).
+// o_sel: where O sits in W's orientation: bit 0 picks Xt[0] / Xt[1] for matrices iterated on their transpose, bit 1
+// picks X (0) or Xt[0] (1) for the others; use_s: multiply O by scal[0] (only when no Newton-Schulz iteration ran).
 // scale_mode: 0 factor = rms_scale*sqrt(max(A,B)); 1 factor = rms_scale*sqrt_hidden; 2 factor = rms_scale*scal[2]
 // (scal[2] = 1/RMS of the stored O, left there by launch_update_rms(..., to_scal = 1)).
 hipError_t launch_apply_update(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles,

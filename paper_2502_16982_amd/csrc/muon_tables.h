@@ -12,7 +12,10 @@ constexpr int kDtypeBF16 = 1;
 // Static per-matrix record (built once at init).
 struct MatDesc {
   void* X;            // m_pad x n_pad, row-major, NS dtype: the iterate in "rows <= cols" orientation
-  void* Xt[2];        // n_pad x m_pad: its transpose, ping-pong pair
+  void* Xt[2];        // fp32 path: n_pad x m_pad, the iterate's transpose, ping-pong pair.  bf16 path (one layout of
+                      // the iterate): Xt[0] is the second m_pad x n_pad buffer of the X ping-pong (and receives U in
+                      // W's orientation when no iteration runs), Xt[1] receives O as n_pad x m_pad for matrices that
+                      // are iterated on their transpose
   void* Ag;           // m_pad x m_pad: Gram matrix X X^T
   void* Bp;           // m_pad x m_pad: b*A + c*A*A
   float* partials;    // one partial sum of squares per 64x64 tile
@@ -49,7 +52,7 @@ struct EwTile {
 // The bf16 kernel writes Ct straight from the accumulator layout and C through one extra MFMA transpose,
 // so single-output problems are posed with Ct as the output.
 struct GemmProblem {
-  const void* L;      // M x K, leading dimension ldl
+  const void* L;      // M x K, leading dimension ldl (K-major launches: element (i, k) at L[k * ldl + i])
   const void* R;      // N x K, leading dimension ldr
   const void* E;      // M x N addend at the output position (may be null), leading dimension lde
   const void* Et;     // the same addend stored transposed, N x M, leading dimension ldet (bf16 kernel reads this one)
