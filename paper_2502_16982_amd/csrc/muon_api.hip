@@ -43,7 +43,7 @@ struct MatPlan {
   int tile;         // fine GEMM block tile = padding granule, in elements
   int chunk;
   int ew_tr, ew_tc; // 64x64 tiles in U's orientation (padded)
-  size_t ns_bytes;  // X + 2 Xt + Ag + Bp
+  size_t ns_bytes;  // X + Xt[0] (+ Xt[1], see x_buffers) + Ag + Bp
   size_t part_off;  // first partial (floats)
 };
 
@@ -76,6 +76,9 @@ constexpr int kCoarse = 256;   // block tile of the large bf16 kernel
 // product X' = B' X needs no addend (a third of its epilogue's memory traffic).  B's diagonal is rounded to bf16
 // once either way; for tiny matrices, where the diagonal carries most of the product, the explicit addend is kept.
 bool folds_identity(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16 && q.m >= 64; }
+// Iterate-sized buffers per matrix: X and Xt[0] always; Xt[1] on the fp32 path (transpose ping-pong) and, on the
+// bf16 path, only for matrices iterated on their transpose (it receives O in W's orientation).
+int x_buffers(const MatPlan& q, int ns_dtype) { return (ns_dtype != MUON_BF16 || q.transposed) ? 3 : 2; }
 
 // Workgroups are handed to the 8 accelerator dies (XCDs, each with a private L2) round-robin by workgroup index:
 // entry b of a tile table runs on XCD b % 8.  Tiles that share operand panels are therefore dealt to the same
@@ -160,7 +163,7 @@ void plan_matrices(const muon_param* p, int n, int ns_dtype, std::vector<MatPlan
     const int ap = q.transposed ? q.np : q.mp, bp = q.transposed ? q.mp : q.np;
     q.ew_tr = ap / kEwTile;
     q.ew_tc = bp / kEwTile;
-    q.ns_bytes = align_up(es * (size_t)q.mp * q.np, 256) * 3 + align_up(es * (size_t)q.mp * q.mp, 256) * 2;
+    q.ns_bytes = align_up(es * (size_t)q.mp * q.np, 256) * x_buffers(q, ns_dtype) + align_up(es * (size_t)q.mp * q.mp, 256) * 2;
     q.part_off = total_partials;
     total_partials += (size_t)q.ew_tr * q.ew_tc;
     q.chunk = 0;
@@ -373,7 +376,8 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
       const size_t xb = align_up(es * (size_t)q.mp * q.np, 256), ab = align_up(es * (size_t)q.mp * q.mp, 256);
       d.X = ns_base + ns_off; ns_off += xb;
       d.Xt[0] = ns_base + ns_off; ns_off += xb;
-      d.Xt[1] = ns_base + ns_off; ns_off += xb;
+      d.Xt[1] = nullptr;
+      if (x_buffers(q, ns_dtype) == 3) { d.Xt[1] = ns_base + ns_off; ns_off += xb; }
       d.Ag = ns_base + ns_off; ns_off += ab;
       d.Bp = ns_base + ns_off; ns_off += ab;
       d.partials = reinterpret_cast<float*>(dev(off_part)) + q.part_off;

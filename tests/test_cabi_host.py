@@ -78,14 +78,16 @@ def test_workspace_bytes_scale_with_dtype_and_cap(binding):
     p = binding.param_array(shapes, [1] * 6, [1] * 6)
     bf = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16)
     f32 = binding.muon_workspace_bytes(p, 6, binding.MUON_F32)
-    # temporaries: 3 m*n + 2 m*m elements per matrix
-    elems = sum(3 * a * b + 2 * min(a, b) ** 2 for a, b in shapes)
-    assert bf >= 2 * elems and bf < 2 * elems * 1.2 + (1 << 22)
-    assert f32 >= 4 * elems and f32 < 4 * elems * 1.2 + (1 << 22)
+    # temporaries per matrix: fp32 path 3 m*n + 2 m*m elements (X, two transposes, A, B); bf16 path 2 m*n + 2 m*m, plus
+    # one more m*n for matrices that are iterated on their transpose (rows > cols)
+    elems32 = sum(3 * a * b + 2 * min(a, b) ** 2 for a, b in shapes)
+    elems16 = sum((3 if a > b else 2) * a * b + 2 * min(a, b) ** 2 for a, b in shapes)
+    assert bf >= 2 * elems16 and bf < 2 * elems16 * 1.2 + (1 << 22)
+    assert f32 >= 4 * elems32 and f32 < 4 * elems32 * 1.2 + (1 << 22)
     capped = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16, max_bytes=bf // 3)
     assert capped < bf and capped % 256 == 0
     tiny = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16, max_bytes=1)
-    one = 2 * (3 * 1024 * 4096 + 2 * 1024 * 1024)
+    one = 2 * (3 * 1024 * 4096 + 2 * 1024 * 1024)     # the largest single matrix is the transposed 4096 x 1024
     assert one <= tiny < one + (1 << 22)
 
 
