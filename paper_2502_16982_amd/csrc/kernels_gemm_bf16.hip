@@ -1,10 +1,13 @@
-// bf16 Newton-Schulz products for gfx950 (Eq. 2 of the paper): grouped "NT" GEMMs
-//     C[i][j] = sum_k L[i][k] * R[j][k]          (bf16 operands, fp32 accumulation on the matrix cores)
-// with a fused epilogue  val = alpha * (beta_acc * acc + beta_e * E[i][j]).  All three products of one
-// iteration have this form once the iterate is kept in both layouts (X and X^T):
-//     Gram       A  = X X^T            L = R = X        (symmetric output)
-//     polynomial B  = b A + c A A      L = R = A        (A symmetric, so A A = A A^T; symmetric output)
-//     apply      X' = a X + B X        L = B, R = X^T   (stores X' and/or X'^T)
+// bf16 Newton-Schulz products for gfx950 (Eq. 2 of the paper): grouped GEMMs
+//     T[i][j] = sum_k L[i][k] * R[j][k]          (bf16 operands, fp32 accumulation on the matrix cores)
+// with a fused epilogue  val = alpha * (beta_acc * acc + beta_e * E[i][j]) (+ a constant on the diagonal), storing
+// T^T (cheap: it is the accumulator layout) and/or T.  R is always contiguous along k; L either contiguous along k
+// or K-major (element (i, k) at L[k * ldl + i]).  With ONE row-major copy of the iterate X (m x n):
+//     Gram       A  = X X^T                L = R = X                   (symmetric output)
+//     polynomial B' = b A + c A A + a I    L = R = A                   (A symmetric; the a X term of the apply
+//                                                                       product travels in B's diagonal)
+//     apply      T  = X'^T = X^T B'        L = X read K-major, R = B'  (stores T^T = X' row-major; T itself only
+//                                                                       where O is wanted transposed)
 // Operands are zero-padded to whole tiles by the producer, so the kernel has no edge handling.
 //
 // Design for CDNA4:
