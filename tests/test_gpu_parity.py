@@ -103,6 +103,17 @@ def test_other_coefficients_and_hyperparameters(dev):
     assert_records(U.run_and_compare(wl, dev, steps=2, hp_over=over), U.TOL_F32_FRO)
 
 
+def test_bf16_six_steps_track_the_oracle(dev):
+    """Six consecutive steps with fresh gradients, both orientations and a padded shape: every step is compared with
+    the oracle run on the library's own state of the step before (momentum and weights carried on the device)."""
+    wl = workloads.custom("six", [(256, 384), (384, 256), (200, 520), (512, 512)], seed_base=43)
+    recs = U.run_and_compare(wl, dev, steps=6, want_rms=True)
+    assert len(recs) == 6 * 4
+    assert_records(recs, U.TOL_BF16_FRO)
+    for r in recs:
+        assert abs(r["rms_gpu"] - r["rms_ref"]) <= 2e-3 * r["rms_ref"], r
+
+
 def test_coefficient_schedule(dev):
     """Iteration k of Eq. 2 with its own (a, b, c): three steps with the paper's triple, then two with the textbook
     order-5 Newton-Schulz polynomial (15, -10, 3)/8; also checks that the order of the triples is honoured."""
