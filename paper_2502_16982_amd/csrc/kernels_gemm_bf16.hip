@@ -212,7 +212,10 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   constexpr int RPS = 2 * FM + FN;               // LDS read instructions per k-step on the K-major path
   // On this path ALL fragment reads are assembly and the waits for them are placed by hand (the compiler neither
   // sees the reads nor counts them): one wait for the k-step-0 fragments before phase B's first MFMA, one for
-  // everything at the end of phase B.  The LDS returns data in issue order.
+  // everything at the end of phase B.  The LDS returns data in issue order.  What this relies on: between a read
+  // and the wait that covers it the compiler must not touch the destination registers (no copy, no spill) - the
+  // fragment arrays are consumed by MFMAs only, after the waits, and the generated main loop is checked to hold
+  // neither moves nor scratch traffic; the parity tests would show a violation as wrong results.
   u32x2 km_half[KSTEPS][FM][2];
   u32x4 km_b[KSTEPS][FN];
   auto read_one = [&](int stage, int kk, int r) {
