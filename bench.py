@@ -14,6 +14,7 @@ average launch duration measured with HIP events on the step's stream inside the
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -123,13 +124,19 @@ def bench_adamw(dev, steps=5):
     return {"elements": n_el, "ms_per_step": ms, "algorithmic_GBs": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
 
 
-def time_workload(name, steps, warmup, max_ws_gib, dev):
+PLANES = {"f32": 1, "bf16": 1, "bf16x2": 2, "bf16x3": 3}     # bf16 arrays per Newton-Schulz temporary
+SEGMENTS = {1: 1, 2: 3, 3: 6}                                 # matrix-core products behind one product of Eq. 2
+
+
+def time_workload(name, steps, warmup, max_ws_gib, dev, ns_dtype=None):
     """W untimed warm-up steps, then exactly `steps` timed steps of the whole hot path over workload `name`
     (inputs generated on the device beforehand), bracketed by device synchronisation.  Per-kernel-class times come
     from HIP events the library records around every launch on the step's stream inside the timed region."""
     import torch
     from paper_2502_16982_amd import binding, workloads
     wl = workloads.workload(name)
+    if ns_dtype is not None:
+        wl = dataclasses.replace(wl, ns_dtype=ns_dtype)
     h = wl.hyper
     tensors = workloads.make_all(wl, dev)
     st = binding.MuonStepper(tensors, ns_dtype=wl.ns_dtype, max_workspace_bytes=int(max_ws_gib * 2 ** 30))
@@ -158,9 +165,9 @@ def time_workload(name, steps, warmup, max_ws_gib, dev):
     nominal = wl.ns_flops()
     gemm_ms = sum(prof[k][0] for k in ("gram", "poly", "apply_poly"))
     gemm_launches = sum(prof[k][1] for k in ("gram", "poly", "apply_poly"))
-    executed = executed_ns_flops(wl, h.ns_steps, 128 if wl.ns_dtype == "bf16" else 64, 256 if wl.ns_dtype == "bf16" else 0)
-
-    bf16 = wl.ns_dtype == "bf16"
+    bf16 = wl.ns_dtype != "f32"              # the matrix-core paths: plain bf16 and the split forms
+    planes = PLANES[wl.ns_dtype]
+    executed = executed_ns_flops(wl, h.ns_steps, 128 if bf16 else 64, 256 if bf16 else 0) * SEGMENTS[planes]
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_VALU_TFLOPS
     if gemm_launches:
         avg_launch_ms = gemm_ms / gemm_launches
@@ -169,7 +176,7 @@ def time_workload(name, steps, warmup, max_ws_gib, dev):
     else:
         avg_launch_ms, flops_per_launch, achieved = 0.0, 0.0, 0.0
     roofline = {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if bf16 else None,
+                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if wl.ns_dtype == "bf16" else None,
                 "kernel": "ns_gemm_bf16_kernel" if bf16 else "ns_gemm_f32_kernel",
                 "avg_launch_ms": avg_launch_ms, "launches_per_step": gemm_launches / max(steps, 1),
                 "nominal_flops_per_launch": flops_per_launch,
@@ -179,7 +186,7 @@ def time_workload(name, steps, warmup, max_ws_gib, dev):
     n_el = wl.n_elements
     g_b = 2 if wl.g_dtype == torch.bfloat16 else 4
     w_b = 2 if wl.w_dtype == torch.bfloat16 else 4
-    x_b = 2 if bf16 else 4
+    x_b = 2 * planes if bf16 else 4
     ew = {}
     for key, bytes_per_el in (("momentum_norm_cast", g_b + 8 + x_b), ("weight_update", 2 * w_b + x_b)):
         ms, cnt = prof[key]
@@ -191,7 +198,7 @@ def time_workload(name, steps, warmup, max_ws_gib, dev):
     st.close()
     del tensors
     torch.cuda.empty_cache()
-    return {"wl": wl, "hyper": h, "bf16": bf16, "elapsed": elapsed, "ms_per_step": ms_per_step, "nominal": nominal,
+    return {"wl": wl, "hyper": h, "bf16": bf16, "planes": planes, "elapsed": elapsed, "ms_per_step": ms_per_step, "nominal": nominal,
             "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
             "executed": executed, "gemm_ms": gemm_ms, "prof": prof, "roofline": roofline, "elementwise": ew, "n_el": n_el,
             "chunks": chunks, "workspace_bytes": ws_bytes}
@@ -206,6 +213,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="time only --config, not the other workloads as well")
     ap.add_argument("--max-workspace-gib", type=float, default=16.0)
+    ap.add_argument("--ns-dtype", choices=sorted(PLANES), default=None,
+                    help="Newton-Schulz arithmetic of --config (default: the workload's own, bf16 for the headline)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -219,7 +228,7 @@ def main() -> int:
         return 2
     binding.lib()
     dev = torch.device("cuda:0")
-    r = time_workload(args.config, args.steps, args.warmup, args.max_workspace_gib, dev)
+    r = time_workload(args.config, args.steps, args.warmup, args.max_workspace_gib, dev, args.ns_dtype)
     wl, h, bf16 = r["wl"], r["hyper"], r["bf16"]
     elapsed, ms_per_step, nominal, executed = r["elapsed"], r["ms_per_step"], r["nominal"], r["executed"]
     gemm_ms, prof, roofline, ew, n_el = r["gemm_ms"], r["prof"], r["roofline"], r["elementwise"], r["n_el"]
@@ -229,7 +238,7 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "dtype": wl.ns_dtype, "data": "synthetic",
         "config": {"workload": wl.name, "matrices": len(wl.shapes), "elements": n_el,
                    "w_dtype": str(wl.w_dtype).replace("torch.", ""), "g_dtype": str(wl.g_dtype).replace("torch.", ""),
                    "momentum_dtype": "float32", "ns_steps": h.ns_steps, "nesterov": bool(h.nesterov),
@@ -257,6 +266,16 @@ def main() -> int:
                 "ns_gemm_tflops_executed": o["roofline"]["executed_tflops"],
                 "avg_gemm_launch_ms": o["roofline"]["avg_launch_ms"], "launches_per_step": o["roofline"]["launches_per_step"],
                 "elementwise": o["elementwise"]})
+        if args.ns_dtype is None:
+            # the accurate matrix-core path on the headline workload: two bf16 planes, three products per product of Eq. 2
+            o = time_workload(args.config, max(2, args.steps // 2), 2, args.max_workspace_gib, dev, "bf16x2")
+            out["accurate_path"] = {
+                "workload": args.config, "ns_dtype": "bf16x2", "ms_per_step": o["ms_per_step"],
+                "ms_per_step_median": o["ms_per_step_median"], "steps_per_s": 1e3 / o["ms_per_step"],
+                "ns_gemm_tflops_nominal": o["roofline"]["achieved"],
+                "matrix_core_tflops_executed": o["roofline"]["executed_tflops"],
+                "avg_gemm_launch_ms": o["roofline"]["avg_launch_ms"], "elementwise": o["elementwise"],
+                "workspace_bytes": o["workspace_bytes"], "chunks": o["chunks"]}
     out["adamw_non_matrix_params"] = bench_adamw(dev)
     torch.cuda.empty_cache()
     if bf16:

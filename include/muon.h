@@ -29,14 +29,20 @@ extern "C" {
 #endif
 
 typedef enum {
-  MUON_F32 = 0,   /* IEEE binary32 */
-  MUON_BF16 = 1   /* bfloat16 (upper 16 bits of a binary32, round-to-nearest-even on store) */
+  MUON_F32 = 0,    /* IEEE binary32 */
+  MUON_BF16 = 1,   /* bfloat16 (upper 16 bits of a binary32, round-to-nearest-even on store) */
+  /* Newton-Schulz arithmetic only (ns_dtype), never a buffer dtype: every iterate and temporary is kept as the
+   * sum of two / three bf16 arrays (value, rounding remainder, remainder of the remainder) and every product
+   * of Eq. 2 runs on the bf16 matrix cores over the plane pairs (i, j) with i + j < planes: 3 / 6 times the
+   * work of MUON_BF16 for about 2^-16 / 2^-23 relative accuracy per product instead of 2^-8. */
+  MUON_BF16X2 = 2,
+  MUON_BF16X3 = 3
 } muon_dtype;
 
 typedef enum {
   MUON_OK = 0,
   MUON_E_INVALID_ARG = -1,         /* null pointer, n <= 0, rows/cols < 1, bad hyper-parameter        */
-  MUON_E_UNSUPPORTED_DTYPE = -2,   /* a dtype field is neither MUON_F32 nor MUON_BF16                  */
+  MUON_E_UNSUPPORTED_DTYPE = -2,   /* a buffer dtype is neither MUON_F32 nor MUON_BF16, or ns_dtype is unknown */
   MUON_E_SHAPE_MISMATCH = -3,      /* the list given to muon_step differs from the one given to init   */
   MUON_E_WORKSPACE_TOO_SMALL = -4, /* workspace cannot hold the tables plus the largest single matrix  */
   MUON_E_HIP = -5,                 /* a HIP runtime call failed (see muon_last_hip_error)              */
@@ -89,7 +95,9 @@ int muon_default_hparams(muon_hparams* hp);
 /*
  * Workspace size for a parameter list.  Only rows/cols/dtypes of `shapes` are read (pointers may be
  * null).  ns_dtype selects the Newton-Schulz arithmetic: MUON_BF16 (bf16 operands, fp32 accumulation;
- * section 2.3 notes bf16 suffices) or MUON_F32.  The Newton-Schulz temporaries of all matrices are
+ * section 2.3 notes bf16 suffices), MUON_F32 (vector ALUs; meant for small matrices), or the split
+ * forms MUON_BF16X2 / MUON_BF16X3 (fp32-class accuracy on the matrix cores, the "more accurate"
+ * direction of section 2.2 at model sizes).  The Newton-Schulz temporaries of all matrices are
  * kept resident when they fit in `max_bytes`; otherwise the list is processed in consecutive chunks
  * that reuse the workspace.  max_bytes == 0 means "no limit".  *out receives the number of bytes to
  * allocate (256-byte aligned device memory); it is never below the minimum that muon_init accepts.

@@ -14,6 +14,8 @@ import os
 from typing import Iterable, List, Optional, Sequence
 
 MUON_F32, MUON_BF16 = 0, 1
+MUON_BF16X2, MUON_BF16X3 = 2, 3     # Newton-Schulz arithmetic only: sums of two / three bf16 planes
+NS_DTYPES = {"f32": MUON_F32, "bf16": MUON_BF16, "bf16x2": MUON_BF16X2, "bf16x3": MUON_BF16X3}
 MUON_SCALE_ADJUSTED_LR, MUON_SCALE_BASELINE, MUON_SCALE_UPDATE_NORM = 0, 1, 2
 MUON_OK = 0
 STATUS_NAMES = {
@@ -259,7 +261,9 @@ class MuonStepper:
         self.tensors: List[tuple] = [tuple(t) for t in tensors]
         if not self.tensors:
             raise MuonError(-1, "empty parameter list")
-        self.ns_dtype = MUON_BF16 if ns_dtype == "bf16" else MUON_F32
+        if ns_dtype not in NS_DTYPES:
+            raise ValueError(f"ns_dtype must be one of {sorted(NS_DTYPES)}")
+        self.ns_dtype = NS_DTYPES[ns_dtype]
         self.n = len(self.tensors)
         self.params = (muon_param * self.n)()
         self.device = self.tensors[0][0].device

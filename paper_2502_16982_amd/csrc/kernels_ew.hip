@@ -95,13 +95,60 @@ __device__ __forceinline__ void store1<u16>(u16* p, float v) { *p = f32_to_bf16(
 
 __device__ __forceinline__ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Newton-Schulz storage with PL planes (PL = 1: one array of XT; PL > 1, XT = bf16: the value is the sum of PL bf16
+// arrays `plane` elements apart, array q holding what the arrays before it left of the fp32 value after rounding).
+template <typename XT, int PL>
+__device__ __forceinline__ void ns_store16(XT* p, size_t plane, const float* in) {
+  if constexpr (PL == 1) {
+    store16<XT>(p, in);
+  } else {
+    float rest[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) rest[i] = in[i];
+#pragma unroll
+    for (int q = 0; q < PL; ++q) {
+      store16<XT>(p + q * plane, rest);
+      if (q + 1 < PL) {
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          const unsigned w = pack2(rest[i], rest[i + 1]);
+          rest[i] -= __uint_as_float(w << 16);              // exact: the rounding error of an fp32 value is an fp32 value
+          rest[i + 1] -= __uint_as_float(w & 0xffff0000u);
+        }
+      }
+    }
+  }
+}
+template <typename XT, int PL>
+__device__ __forceinline__ void ns_load16(const XT* p, size_t plane, float* out) {
+  load16<XT>(p + (PL - 1) * plane, out);
+  if constexpr (PL > 1) {
+#pragma unroll
+    for (int q = PL - 2; q >= 0; --q) {        // smallest plane first
+      float v[16];
+      load16<XT>(p + q * plane, v);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) out[i] += v[i];
+    }
+  }
+}
+template <typename XT, int PL>
+__device__ __forceinline__ float ns_load1(const XT* p, size_t plane) {
+  float v = load1<XT>(p + (PL - 1) * plane);
+  if constexpr (PL > 1) {
+#pragma unroll
+    for (int q = PL - 2; q >= 0; --q) v += load1<XT>(p + q * plane);
+  }
+  return v;
+}
+
 // ------------------------------------------------------------------------------------------------------
 // a1 + a2 (first stage) + a3.  Thread t of a block owns row t/4 and 16 consecutive columns of a 64x64 tile
 // in U's orientation.  GT: gradient element type; XT: Newton-Schulz element type.
 // Writes: M (guarded), the tile of U into the buffer of the same orientation, the transposed tile (through
 // LDS) into the buffer of the other orientation, both zero-filled outside A x B, and one partial sum of U^2.
 // ------------------------------------------------------------------------------------------------------
-template <typename GT, typename XT>
+template <typename GT, typename XT, int PL>
 __device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float mu, int nesterov,
                                               bool both, float (*lds)[kEwTile + 1], float* red) {
   const int tid = threadIdx.x;
@@ -151,7 +198,7 @@ __device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& p
   const int pitch_flip = d.transposed ? d.np : d.mp;
 
   const bool write_same = both || !d.transposed, write_flip = both || d.transposed;
-  if (write_same) store16<XT>(same + (size_t)r * pitch_same + c0, u);
+  if (write_same) ns_store16<XT, PL>(same + (size_t)r * pitch_same + c0, (size_t)d.x_plane, u);
 
   const int lr_ = tid >> 2, lc0 = (tid & 3) * 16;
 #pragma unroll
@@ -161,12 +208,12 @@ __device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& p
   const int fc = tid >> 2, fr0 = (tid & 3) * 16;   // row of U^T (= column of U), 16 consecutive columns of U^T
 #pragma unroll
   for (int i = 0; i < 16; ++i) t[i] = lds[fc][fr0 + i];
-  if (write_flip) store16<XT>(flip + (size_t)(tc * kEwTile + fc) * pitch_flip + tr * kEwTile + fr0, t);
+  if (write_flip) ns_store16<XT, PL>(flip + (size_t)(tc * kEwTile + fc) * pitch_flip + tr * kEwTile + fr0, (size_t)d.x_plane, t);
 
   if (tid == 0) d.partials[tr * d.ew_tiles_c + tc] = total;
 }
 
-template <typename XT>
+template <typename XT, int PL>
 __global__ __launch_bounds__(256) void momentum_norm_cast_kernel(const MatDesc* __restrict__ mats,
                                                                   const MatPtrs* __restrict__ ptrs,
                                                                   const EwTile* __restrict__ tiles, float mu,
@@ -179,9 +226,9 @@ __global__ __launch_bounds__(256) void momentum_norm_cast_kernel(const MatDesc* 
   for (int k = 0; k < t.count; ++k) {
     if (k) __syncthreads();     // the LDS tile and the reduction scratch are reused
     if (d.g_dtype == kDtypeBF16)
-      momentum_tile<u16, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, both != 0, lds, red);
+      momentum_tile<u16, XT, PL>(d, pt, t.tr, t.tc + k, mu, nesterov, both != 0, lds, red);
     else
-      momentum_tile<float, XT>(d, pt, t.tr, t.tc + k, mu, nesterov, both != 0, lds, red);
+      momentum_tile<float, XT, PL>(d, pt, t.tr, t.tc + k, mu, nesterov, both != 0, lds, red);
   }
 }
 
@@ -218,7 +265,7 @@ __device__ __forceinline__ const void* o_source(const MatDesc& d, int o_sel) {
   return (o_sel & 2) ? d.Xt[0] : d.X;
 }
 
-template <typename WT, typename XT, bool UPDATE>
+template <typename WT, typename XT, int PL, bool UPDATE>
 __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float lr, float wd,
                                            float scale, int o_sel, float* red) {
   const int tid = threadIdx.x;
@@ -228,6 +275,7 @@ __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, 
   WT* w = static_cast<WT*>(pt.w);
   const XT* o = static_cast<const XT*>(o_source(d, o_sel));
   const int pitch = d.transposed ? d.mp : d.np;
+  const size_t plane = (size_t)d.x_plane;
   float ss = 0.f;
   if (r < A && c0 < B) {
     const size_t base = (size_t)r * (size_t)B + (size_t)c0;
@@ -235,19 +283,19 @@ __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, 
     if (!UPDATE) {
       if (c0 + 16 <= B) {
         float ov[16];
-        load16<XT>(op, ov);
+        ns_load16<XT, PL>(op, plane, ov);
 #pragma unroll
         for (int i = 0; i < 16; ++i) ss = fmaf(ov[i], ov[i], ss);
       } else {
         for (int i = 0; i < 16 && c0 + i < B; ++i) {
-          const float ov = load1<XT>(op + i);
+          const float ov = ns_load1<XT, PL>(op + i, plane);
           ss = fmaf(ov, ov, ss);
         }
       }
     } else if ((c0 + 16 <= B) && ((B & 7) == 0) && aligned16(w)) {
       float wv[16], ov[16];
       load16<WT>(w + base, wv);
-      load16<XT>(op, ov);
+      ns_load16<XT, PL>(op, plane, ov);
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         ss = fmaf(ov[i], ov[i], ss);
@@ -257,7 +305,7 @@ __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, 
       store16<WT>(w + base, wv);
     } else {
       for (int i = 0; i < 16 && c0 + i < B; ++i) {
-        const float ov = load1<XT>(op + i);
+        const float ov = ns_load1<XT, PL>(op + i, plane);
         const float wv = load1<WT>(w + base + i);
         ss = fmaf(ov, ov, ss);
         const float t = fmaf(wd, wv, scale * ov);
@@ -269,7 +317,7 @@ __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, 
   if (tid == 0) d.partials[tr * d.ew_tiles_c + tc] = total;
 }
 
-template <typename XT>
+template <typename XT, int PL>
 __global__ __launch_bounds__(256) void apply_update_kernel(const MatDesc* __restrict__ mats, const MatPtrs* __restrict__ ptrs,
                                                             const EwTile* __restrict__ tiles, float lr, float wd,
                                                             float rms_scale, int scale_mode, float sqrt_hidden, int o_sel,
@@ -289,14 +337,14 @@ __global__ __launch_bounds__(256) void apply_update_kernel(const MatDesc* __rest
   for (int k = 0; k < t.count; ++k) {
     if (k) __syncthreads();     // the reduction scratch is reused
     if (d.w_dtype == kDtypeBF16)
-      apply_tile<u16, XT, true>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
+      apply_tile<u16, XT, PL, true>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
     else
-      apply_tile<float, XT, true>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
+      apply_tile<float, XT, PL, true>(d, pt, t.tr, t.tc + k, lr, wd, scale, o_sel, red);
   }
 }
 
 // Per-tile sums of O^2 only (first pass of the "Update Norm" variant, Eq. 6).
-template <typename XT>
+template <typename XT, int PL>
 __global__ __launch_bounds__(256) void update_sumsq_kernel(const MatDesc* __restrict__ mats, const EwTile* __restrict__ tiles,
                                                             int o_sel) {
   __shared__ float red[4];
@@ -305,7 +353,7 @@ __global__ __launch_bounds__(256) void update_sumsq_kernel(const MatDesc* __rest
   const MatPtrs none{nullptr, nullptr, nullptr};
   for (int k = 0; k < t.count; ++k) {
     if (k) __syncthreads();
-    apply_tile<float, XT, false>(d, none, t.tr, t.tc + k, 0.f, 0.f, 0.f, o_sel, red);
+    apply_tile<float, XT, PL, false>(d, none, t.tr, t.tc + k, 0.f, 0.f, 0.f, o_sel, red);
   }
 }
 
@@ -333,7 +381,7 @@ __global__ __launch_bounds__(256) void update_rms_kernel(const MatDesc* __restri
   }
 }
 
-template <typename XT, typename DT>
+template <typename XT, int PL, typename DT>
 __global__ __launch_bounds__(256) void read_update_kernel(const MatDesc* __restrict__ mats, int mat, int o_sel, int use_s,
                                                            DT* __restrict__ dst) {
   const MatDesc d = mats[mat];
@@ -343,19 +391,28 @@ __global__ __launch_bounds__(256) void read_update_kernel(const MatDesc* __restr
   const size_t total = (size_t)d.rows * (size_t)d.cols;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
     const size_t r = i / (size_t)d.cols, c = i % (size_t)d.cols;
-    store1<DT>(dst + i, s * load1<XT>(o + r * pitch + c));
+    store1<DT>(dst + i, s * ns_load1<XT, PL>(o + r * pitch + c, (size_t)d.x_plane));
   }
 }
 
 }  // namespace
 
+// ns_dtype -> (element type, planes): fp32; bf16; bf16 x 2 planes; bf16 x 3 planes
+#define MUON_NS_DISPATCH(ns_dtype, CALL)                 \
+  switch (ns_dtype) {                                    \
+    case kDtypeF32: { CALL(float, 1); break; }           \
+    case kDtypeBF16: { CALL(u16, 1); break; }            \
+    case kDtypeBF16X2: { CALL(u16, 2); break; }          \
+    case kDtypeBF16X3: { CALL(u16, 3); break; }          \
+    default: return hipErrorInvalidValue;                \
+  }
+
 hipError_t launch_momentum_norm_cast(const MatDesc* mats, const MatPtrs* ptrs, const EwTile* tiles, int n_tiles, float mu,
                                      int nesterov, int both_layouts, int ns_dtype, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
-  if (ns_dtype == kDtypeBF16)
-    momentum_norm_cast_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov, both_layouts);
-  else
-    momentum_norm_cast_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov, both_layouts);
+#define MUON_CALL(XT, PL) momentum_norm_cast_kernel<XT, PL><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, mu, nesterov, both_layouts)
+  MUON_NS_DISPATCH(ns_dtype, MUON_CALL)
+#undef MUON_CALL
   return hipGetLastError();
 }
 
@@ -369,19 +426,18 @@ hipError_t launch_apply_update(const MatDesc* mats, const MatPtrs* ptrs, const E
                                float rms_scale, int scale_mode, float sqrt_hidden, int o_sel, int use_s, int ns_dtype,
                                hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
-  if (ns_dtype == kDtypeBF16)
-    apply_update_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, scale_mode, sqrt_hidden, o_sel, use_s);
-  else
-    apply_update_kernel<float><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, scale_mode, sqrt_hidden, o_sel, use_s);
+#define MUON_CALL(XT, PL) \
+  apply_update_kernel<XT, PL><<<n_tiles, 256, 0, s>>>(mats, ptrs, tiles, lr, wd, rms_scale, scale_mode, sqrt_hidden, o_sel, use_s)
+  MUON_NS_DISPATCH(ns_dtype, MUON_CALL)
+#undef MUON_CALL
   return hipGetLastError();
 }
 
 hipError_t launch_update_sumsq(const MatDesc* mats, const EwTile* tiles, int n_tiles, int o_sel, int ns_dtype, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
-  if (ns_dtype == kDtypeBF16)
-    update_sumsq_kernel<u16><<<n_tiles, 256, 0, s>>>(mats, tiles, o_sel);
-  else
-    update_sumsq_kernel<float><<<n_tiles, 256, 0, s>>>(mats, tiles, o_sel);
+#define MUON_CALL(XT, PL) update_sumsq_kernel<XT, PL><<<n_tiles, 256, 0, s>>>(mats, tiles, o_sel)
+  MUON_NS_DISPATCH(ns_dtype, MUON_CALL)
+#undef MUON_CALL
   return hipGetLastError();
 }
 
@@ -394,16 +450,14 @@ hipError_t launch_update_rms(const MatDesc* mats, int first_mat, int n_mats, int
 hipError_t launch_read_update(const MatDesc* mats, int mat, int o_sel, int use_s, int ns_dtype, void* dst, int dst_dtype,
                               hipStream_t s) {
   const int grid = 1024;
-  if (ns_dtype == kDtypeBF16) {
-    if (dst_dtype == kDtypeBF16)
-      read_update_kernel<u16, u16><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<u16*>(dst));
-    else
-      read_update_kernel<u16, float><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<float*>(dst));
+  if (dst_dtype == kDtypeBF16) {
+#define MUON_CALL(XT, PL) read_update_kernel<XT, PL, u16><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<u16*>(dst))
+    MUON_NS_DISPATCH(ns_dtype, MUON_CALL)
+#undef MUON_CALL
   } else {
-    if (dst_dtype == kDtypeBF16)
-      read_update_kernel<float, u16><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<u16*>(dst));
-    else
-      read_update_kernel<float, float><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<float*>(dst));
+#define MUON_CALL(XT, PL) read_update_kernel<XT, PL, float><<<grid, 256, 0, s>>>(mats, mat, o_sel, use_s, static_cast<float*>(dst))
+    MUON_NS_DISPATCH(ns_dtype, MUON_CALL)
+#undef MUON_CALL
   }
   return hipGetLastError();
 }

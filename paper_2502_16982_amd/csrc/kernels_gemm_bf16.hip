@@ -96,9 +96,25 @@ __device__ long long g_dbg_clk[8192 * 2];
 #define DBG_E(slot) do {} while (0)
 #endif
 
+// Split operands (PL > 1 planes): every matrix is the sum of PL bf16 arrays ("planes", plane q at element offset
+// q * plane stride from the base pointer), each holding what the planes before it left of the fp32 value after
+// rounding to bf16, i.e. about 2^-8 of its predecessor.  A product of two such sums is taken over the plane pairs
+// (i, j) with i + j < PL - the pairs left out are below 2^(-8 PL) of the result - as ONE K loop over
+// PL (PL + 1) / 2 segments that all accumulate into the same fp32 registers, smallest terms first.
+constexpr int seg_count(int pl) { return pl * (pl + 1) / 2; }
+// plane of the L (which = 0) or R (which = 1) operand in segment s: pairs by decreasing i + j, then decreasing i
+constexpr int seg_plane(int pl, int s, int which) {
+  int n = 0;
+  for (int total = pl - 1; total >= 0; --total)
+    for (int i = total; i >= 0; --i, ++n)
+      if (n == s) return which == 0 ? i : total - i;
+  return 0;
+}
+
 // LKM: the L operand is stored K-major (element (i, k) at L[k * ldl + i], i.e. the product is L^T-by-R^T of two
 // row-major arrays); its MFMA fragments then come from LDS through the transposing read ds_read_b64_tr_b16.
-template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB, bool LKM>
+// PL: number of bf16 planes per matrix (1: plain bf16).
+template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB, bool LKM, int PL>
 __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const GemmProblem* __restrict__ probs,
                                                                             const GemmTile* __restrict__ tiles,
                                                                             float beta_acc, float beta_e, int alpha_idx,
@@ -110,6 +126,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   constexpr int NLOAD = LI + RI;
   constexpr int STAGE_B = (BM + BN) * ROWB;        // bytes per stage
   constexpr int KSTEPS = BK / 16;                  // MFMA k-steps per slab
+  constexpr int NSEG = seg_count(PL);              // K-loop segments (plane pairs)
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
   static_assert(NW % 2 == 0 && NSTAGE == 2 && NLOAD < 32, "pipeline shape");
   static_assert(4 * FM == WTM / 8 && (WTM / 8 & (WTM / 8 - 1)) == 0 && BM / 8 >= 16, "slot addressing: 4i+q and wm*WTM/8 use disjoint bits");
@@ -143,16 +160,33 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   const u16* rsrc = static_cast<const u16*>(p.R) + (size_t)(col0 + dma_row) * p.ldr + dma_chunk * 8;
   const size_t lstep = (size_t)(LKM ? NW * RPK : 8 * NW) * p.ldl, rstep = (size_t)(8 * NW) * p.ldr;
   const size_t lslab = LKM ? (size_t)BK * p.ldl : (size_t)BK;      // elements from one K slab of L to the next
+  const int KT1 = p.K / BK;                        // slabs per segment
   // requests DMA instructions [first, first + count) of slab kt (instructions 0..LI-1 fetch L rows, the rest R rows)
   auto request_part = [&](int kt, int stage, auto first_tag, auto count_tag) {
     constexpr int FIRST = decltype(first_tag)::value, COUNT = decltype(count_tag)::value;
     unsigned char* base = smem + stage * STAGE_B + wave * 1024;
+    size_t loff, roff;                             // element offsets of slab kt in L and R (wave-uniform)
+    if constexpr (PL == 1) {
+      loff = (size_t)kt * lslab;
+      roff = (size_t)kt * BK;
+    } else {
+      int seg = 0, kl = kt;
+#pragma unroll
+      for (int sgm = 1; sgm < NSEG; ++sgm)
+        if (kt >= sgm * KT1) { seg = sgm; kl = kt - sgm * KT1; }
+      int lpl = seg_plane(PL, 0, 0), rpl = seg_plane(PL, 0, 1);
+#pragma unroll
+      for (int sgm = 1; sgm < NSEG; ++sgm)
+        if (seg == sgm) { lpl = seg_plane(PL, sgm, 0); rpl = seg_plane(PL, sgm, 1); }
+      loff = (size_t)kl * lslab + (size_t)lpl * (size_t)p.l_plane;
+      roff = (size_t)kl * BK + (size_t)rpl * (size_t)p.r_plane;
+    }
 #pragma unroll
     for (int n = FIRST; n < FIRST + COUNT; ++n) {
       if (n < LI)
-        __builtin_amdgcn_global_load_lds((gptr)(lsrc + n * lstep + (size_t)kt * lslab), (lptr)(base + n * NW * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr)(lsrc + n * lstep + loff), (lptr)(base + n * NW * 1024), 16, 0, 0);
       else
-        __builtin_amdgcn_global_load_lds((gptr)(rsrc + (n - LI) * rstep + (size_t)kt * BK),
+        __builtin_amdgcn_global_load_lds((gptr)(rsrc + (n - LI) * rstep + roff),
                                          (lptr)(base + BM * ROWB + (n - LI) * NW * 1024), 16, 0, 0);
     }
   };
@@ -253,7 +287,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   //      barrier #1: nobody reads stage `cur` any more
   //   C  MFMAs of k-steps 1, 2          | the requests of slab kt+2, into stage `cur`
   //      wait until slab kt+1 (requested one iteration ago) has landed, barrier #2.
-  const int KT = p.K / BK;
+  const int KT = NSEG * KT1;
   request_part(0, 0, Zero{}, AllN{});
   if (KT > 1) { request_part(1, 1, Zero{}, HeadN{}); wait_vmcnt<HEAD>(); } else { wait_vmcnt<0>(); }
   __syncthreads();
@@ -278,11 +312,12 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   constexpr int RPI_T = 64 / CPT;                // image rows per wave-level DMA instruction / per 64 lanes
   constexpr int TI = BN / RPI_T / NW;            // DMA instructions (or 64-lane store groups) per wave
   constexpr int IPS = STAGE_B / 1024 / NW;       // image DMA instructions per wave that land in one pipeline stage
-  auto et_request = [&](int region) {            // requests the part of the image that overlays pipeline stage `region`
+  auto et_request = [&](int region, int plane = 0) {   // requests the part of the image that overlays pipeline stage `region`
     if (region * IPS >= TI) return;
     const int idx0 = region * IPS * NW + wave;
     const int c0 = idx0 * RPI_T + lane / CPT;
     const u16* src = Et + (size_t)(col0 + c0) * p.ldet + row0;
+    if constexpr (PL > 1) src += (size_t)plane * (size_t)p.et_plane;
     unsigned char* dstl = smem + idx0 * 1024;
 #pragma unroll
     for (int i = 0; i < (IPS < TI ? IPS : TI); ++i) {
@@ -370,7 +405,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       request_part(kt + 2, cur, Zero{}, HeadN{});
     }
     // C
-    if (!REFILL && !SYNC && Et) et_request(cur ^ 1);
+    if (PL == 1 && !REFILL && !SYNC && Et) et_request(cur ^ 1);
 #pragma unroll
     for (int kk = 1; kk < KSTEPS - 1; ++kk) {
       if (LKM) {
@@ -441,11 +476,13 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     ldct = p.ldc;
     if (tile.ti == tile.tj) C = nullptr;
   }
+  if constexpr (PL == 1) {
   if (Et) {
     et_request(cur ^ 1);        // `cur` was flipped after the last iteration: cur^1 is the stage that iteration still read
     DBG_E(2);
     wait_vmcnt<0>();
     __syncthreads();
+  }
   }
   DBG_E(3);
 
@@ -501,6 +538,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       __builtin_amdgcn_sched_barrier(0);
     }
   };
+  if constexpr (PL == 1) {
   if (Et) combine(std::true_type{}); else combine(std::false_type{});
 
   DBG_E(4);
@@ -595,54 +633,232 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  } else {
+    // ---- split operands: val = alpha * (beta_acc * acc + beta_e * sum_q E_q) (+ diagonal constant) is formed in
+    // the accumulator registers in fp32; plane q of the outputs is bf16(val_q) with val_0 = val and
+    // val_{q+1} = val_q - bf16(val_q) (exact in fp32).  Every plane takes the same route through the LDS images
+    // as the single plane of the plain path; nothing is overlapped here - three to six times the matrix-core work
+    // stands against this epilogue.
+    const size_t ctpl = (size_t)(p.symmetric ? p.c_plane : p.ct_plane), cpl = (size_t)p.c_plane;
+    auto pack4 = [](float x0, float x1, float x2, float x3) -> u32x2 {
+      const f32x2 lo = {x0, x1}, hi = {x2, x3};
+      u32x2 w;
+      w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
+      w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2));
+      return w;
+    };
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] *= ab_acc;
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    if (BM == BN && FM == FN) {
+      if (diag_here) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][i < FN ? i : 0][v] += (fr == 8 * (v >> 2) + 4 * fh + (v & 3)) ? diag_add : 0.f;
+      }
+    }
+    if (Et) {
+#pragma unroll 1
+      for (int q = 0; q < PL; ++q) {
+        if (q) __syncthreads();                  // every lane has taken its pieces of the previous plane's image
+        et_request(0, q);
+        et_request(1, q);
+        wait_vmcnt<0>();
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+              const u32x2 e2 = *reinterpret_cast<const u32x2*>(slot_of(i, j, qq));
+              acc[i][j][4 * qq + 0] = fmaf(ab_e, __uint_as_float(e2.x << 16), acc[i][j][4 * qq + 0]);
+              acc[i][j][4 * qq + 1] = fmaf(ab_e, __uint_as_float(e2.x & 0xffff0000u), acc[i][j][4 * qq + 1]);
+              acc[i][j][4 * qq + 2] = fmaf(ab_e, __uint_as_float(e2.y << 16), acc[i][j][4 * qq + 2]);
+              acc[i][j][4 * qq + 3] = fmaf(ab_e, __uint_as_float(e2.y & 0xffff0000u), acc[i][j][4 * qq + 3]);
+              if (qq == 3) __builtin_amdgcn_sched_barrier(0);   // one MFMA tile at a time: keeps the register count down
+            }
+      }
+    }
+    // store-out of the transposed image [BN][BM] and of the row-major image [BM][BN]: 16 bytes per lane, coalesced
+    constexpr int SBT = TI < 8 ? TI : 8;
+    constexpr int CSTEP = NW * RPI_T, PERIOD_T = CPT / CSTEP > 0 ? CPT / CSTEP : 1;
+    auto store_ct = [&](u16* base) {
+      const int c_first = wave * RPI_T + lane / CPT;
+      u16* dst[PERIOD_T];
+#pragma unroll
+      for (int k = 0; k < PERIOD_T; ++k) {
+        const int c = c_first + k * CSTEP;
+        dst[k] = base + (size_t)(col0 + c) * ldct + row0 + ((lane % CPT) ^ (c & (CPT - 1))) * 8;
+      }
+      const size_t dstep = (size_t)(CSTEP * PERIOD_T) * ldct;
+#pragma unroll
+      for (int i0 = 0; i0 < TI; i0 += SBT) {
+        u32x4 v[SBT];
+#pragma unroll
+        for (int u = 0; u < SBT; ++u) v[u] = *reinterpret_cast<const u32x4*>(smem + ((i0 + u) * NW + wave) * 1024 + lane * 16);
+#pragma unroll
+        for (int u = 0; u < SBT; ++u) {
+          const int i = i0 + u;
+          *(gvec_ptr)(dst[i % PERIOD_T] + (size_t)(i / PERIOD_T) * dstep) = v[u];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    constexpr int CPR = BN / 8, RPI_C = 64 / CPR, CI = BM / RPI_C / NW;
+    constexpr int SBC = CI < 8 ? CI : 8;
+    constexpr int RSTEP = NW * RPI_C, PERIOD_C = CPR / RSTEP > 0 ? CPR / RSTEP : 1;
+    auto store_c = [&](u16* base) {
+      const int r_first = wave * RPI_C + lane / CPR;
+      u16* dst[PERIOD_C];
+#pragma unroll
+      for (int k = 0; k < PERIOD_C; ++k) {
+        const int r = r_first + k * RSTEP;
+        dst[k] = base + (size_t)(row0 + r) * p.ldc + col0 + ((lane % CPR) ^ (r & (CPR - 1))) * 8;
+      }
+      const size_t dstep = (size_t)(RSTEP * PERIOD_C) * p.ldc;
+#pragma unroll
+      for (int i0 = 0; i0 < CI; i0 += SBC) {
+        u32x4 v[SBC];
+#pragma unroll
+        for (int u = 0; u < SBC; ++u) v[u] = *reinterpret_cast<const u32x4*>(smem + ((i0 + u) * NW + wave) * 1024 + lane * 16);
+#pragma unroll
+        for (int u = 0; u < SBC; ++u) {
+          const int i = i0 + u;
+          *(gvec_ptr)(dst[i % PERIOD_C] + (size_t)(i / PERIOD_C) * dstep) = v[u];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    bf16x8 sel[2];                               // 0/1 selector of the MFMA transpose (see the plain path)
+#pragma unroll
+    for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const int row = 16 * sx + 4 * fh + (t < 4 ? t : 4 + t);
+        sel[sx][t] = (__bf16)(fr == row ? 1.0f : 0.0f);
+      }
+#pragma unroll 1
+    for (int q = 0; q < PL; ++q) {
+      if (Ct) {
+        __syncthreads();                         // the image is free (addend consumed / previous plane stored)
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+              *reinterpret_cast<u32x2*>(slot_of(i, j, qq)) =
+                  pack4(acc[i][j][4 * qq], acc[i][j][4 * qq + 1], acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]);
+              if (qq == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+        __syncthreads();
+        store_ct(Ct + (size_t)q * ctpl);
+      }
+      if (C) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j) {
+            f32x16 d;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d[v] = 0.f;
+#pragma unroll
+            for (int sx = 0; sx < 2; ++sx) {
+              const u32x2 w0 = pack4(acc[i][j][8 * sx], acc[i][j][8 * sx + 1], acc[i][j][8 * sx + 2], acc[i][j][8 * sx + 3]);
+              const u32x2 w1 = pack4(acc[i][j][8 * sx + 4], acc[i][j][8 * sx + 5], acc[i][j][8 * sx + 6], acc[i][j][8 * sx + 7]);
+              const u32x4 raw = {w0.x, w0.y, w1.x, w1.y};
+              d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), sel[sx], d, 0, 0, 0);
+            }
+            const int r = wm * WTM + i * 32 + fr;
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+              const int lchunk = (wn * WTN + j * 32) / 8 + qq;
+              *reinterpret_cast<u32x2*>(smem + r * (BN * 2) + ((lchunk ^ (r & (CPR - 1))) * 16) + fh * 8) =
+                  pack4(d[4 * qq], d[4 * qq + 1], d[4 * qq + 2], d[4 * qq + 3]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        __syncthreads();
+        store_c(C + (size_t)q * cpl);
+      }
+      if (q + 1 < PL) {                          // what this plane left of the value
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+              const u32x2 w = pack4(acc[i][j][4 * qq], acc[i][j][4 * qq + 1], acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]);
+              acc[i][j][4 * qq + 0] -= __uint_as_float(w.x << 16);
+              acc[i][j][4 * qq + 1] -= __uint_as_float(w.x & 0xffff0000u);
+              acc[i][j][4 * qq + 2] -= __uint_as_float(w.y << 16);
+              acc[i][j][4 * qq + 3] -= __uint_as_float(w.y & 0xffff0000u);
+              if (qq == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+      }
+    }
+  }
   DBG_E(9);
   DBG_BLK(2);
   DBG_BLK(3);
 }
 
-// ---- instantiations: {tile, waves, stages, waves per SIMD} per GemmShape ----
-#define GEMM_S128 ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, false>
-#define GEMM_S128K ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, true>
-#ifdef MUON_GEMM_256_W8
-#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 4, 2, 2, false>
-#define GEMM_S256K ns_gemm_bf16_kernel<256, 256, 2, 4, 2, 2, true>
-#define GEMM_S256_THREADS 512
-#else
-#define GEMM_S256 ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, false>
-#define GEMM_S256K ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, true>
-#define GEMM_S256_THREADS 256
-#endif
+// ---- instantiations: {tile, waves, stages, waves per SIMD} per GemmShape, x {L contiguous along k, K-major} x planes ----
 constexpr size_t kLds128 = TileCfg<128, 128>::lds_bytes(2);
 constexpr size_t kLds256 = TileCfg<256, 256>::lds_bytes(2);
+constexpr int kMaxPlanes = 3;
+
+template <bool LKM, int PL>
+hipError_t setup_pair() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, LKM, PL>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds128);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, LKM, PL>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds256);
+}
+
+template <bool LKM, int PL>
+void launch_one(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc, float beta_e,
+                int alpha_idx, float diag_add, hipStream_t s) {
+  if (shape == kShape128)
+    ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, LKM, PL><<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+  else
+    ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, LKM, PL><<<n_tiles, 256, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+}
 
 }  // namespace
 
 hipError_t gemm_setup() {
-  const void* k128[] = {reinterpret_cast<const void*>(&GEMM_S128), reinterpret_cast<const void*>(&GEMM_S128K)};
-  const void* k256[] = {reinterpret_cast<const void*>(&GEMM_S256), reinterpret_cast<const void*>(&GEMM_S256K)};
-  for (const void* f : k128) {
-    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds128);
-    if (e != hipSuccess) return e;
-  }
-  for (const void* f : k256) {
-    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds256);
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
+  hipError_t e = setup_pair<false, 1>();
+  if (e == hipSuccess) e = setup_pair<true, 1>();
+  if (e == hipSuccess) e = setup_pair<false, 2>();
+  if (e == hipSuccess) e = setup_pair<true, 2>();
+  if (e == hipSuccess) e = setup_pair<false, 3>();
+  if (e == hipSuccess) e = setup_pair<true, 3>();
+  return e;
 }
 
 hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
-                            float beta_e, int alpha_idx, float diag_add, int l_kmajor, hipStream_t s) {
+                            float beta_e, int alpha_idx, float diag_add, int l_kmajor, int planes, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
-  if (shape == kShape128) {
-    if (l_kmajor) GEMM_S128K<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
-    else GEMM_S128<<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
-  } else if (shape == kShape256) {
-    if (l_kmajor) GEMM_S256K<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
-    else GEMM_S256<<<n_tiles, GEMM_S256_THREADS, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
-  } else {
-    return hipErrorInvalidValue;
-  }
+  if ((shape != kShape128 && shape != kShape256) || planes < 1 || planes > kMaxPlanes) return hipErrorInvalidValue;
+#define MUON_GEMM_CASE(K, P)                                                                                     \
+  if ((l_kmajor != 0) == K && planes == P) launch_one<K, P>(shape, probs, tiles, n_tiles, beta_acc, beta_e, alpha_idx, diag_add, s)
+  MUON_GEMM_CASE(false, 1);
+  MUON_GEMM_CASE(true, 1);
+  MUON_GEMM_CASE(false, 2);
+  MUON_GEMM_CASE(true, 2);
+  MUON_GEMM_CASE(false, 3);
+  MUON_GEMM_CASE(true, 3);
+#undef MUON_GEMM_CASE
   return hipGetLastError();
 }
 

@@ -76,9 +76,14 @@ constexpr int kCoarse = 256;   // block tile of the large bf16 kernel
 // product X' = B' X needs no addend (a third of its epilogue's memory traffic).  B's diagonal is rounded to bf16
 // once either way; for tiny matrices, where the diagonal carries most of the product, the explicit addend is kept.
 bool folds_identity(const MatPlan& q, int ns_dtype) { return ns_dtype == MUON_BF16 && q.m >= 64; }
+// The matrix-core paths: plain bf16 and the split forms (every temporary = sum of 2 or 3 bf16 planes, stored one after
+// the other; all of them share the bf16 planner, tile tables and kernels).  The split forms keep the explicit a*X
+// addend: folded into B's diagonal it would be rounded at the diagonal's magnitude (a = 3.44), not the iterate's.
+bool on_matrix_cores(int ns_dtype) { return ns_dtype != MUON_F32; }
+int planes_of(int ns_dtype) { return ns_dtype == MUON_BF16X2 ? 2 : ns_dtype == MUON_BF16X3 ? 3 : 1; }
 // Iterate-sized buffers per matrix: X and Xt[0] always; Xt[1] on the fp32 path (transpose ping-pong) and, on the
 // bf16 path, only for matrices iterated on their transpose (it receives O in W's orientation).
-int x_buffers(const MatPlan& q, int ns_dtype) { return (ns_dtype != MUON_BF16 || q.transposed) ? 3 : 2; }
+int x_buffers(const MatPlan& q, int ns_dtype) { return (!on_matrix_cores(ns_dtype) || q.transposed) ? 3 : 2; }
 
 // Workgroups are handed to the 8 accelerator dies (XCDs, each with a private L2) round-robin by workgroup index:
 // entry b of a tile table runs on XCD b % 8.  Tiles that share operand panels are therefore dealt to the same
@@ -135,7 +140,8 @@ size_t deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTil
 
 int validate_shapes(const muon_param* p, int32_t n, int32_t ns_dtype) {
   if (!p || n <= 0) return MUON_E_INVALID_ARG;
-  if (ns_dtype != MUON_F32 && ns_dtype != MUON_BF16) return MUON_E_UNSUPPORTED_DTYPE;
+  if (ns_dtype != MUON_F32 && ns_dtype != MUON_BF16 && ns_dtype != MUON_BF16X2 && ns_dtype != MUON_BF16X3)
+    return MUON_E_UNSUPPORTED_DTYPE;
   for (int i = 0; i < n; ++i) {
     if (p[i].rows < 1 || p[i].cols < 1 || p[i].rows > kMaxDim || p[i].cols > kMaxDim) return MUON_E_INVALID_ARG;
     if ((p[i].w_dtype != MUON_F32 && p[i].w_dtype != MUON_BF16) || (p[i].g_dtype != MUON_F32 && p[i].g_dtype != MUON_BF16))
@@ -147,7 +153,7 @@ int validate_shapes(const muon_param* p, int32_t n, int32_t ns_dtype) {
 void plan_matrices(const muon_param* p, int n, int ns_dtype, std::vector<MatPlan>& out, size_t& total_partials) {
   out.resize(n);
   total_partials = 0;
-  const size_t es = ns_dtype == MUON_BF16 ? 2 : 4;
+  const size_t es = on_matrix_cores(ns_dtype) ? 2 : 4;
   for (int i = 0; i < n; ++i) {
     MatPlan& q = out[i];
     q.rows = p[i].rows;
@@ -157,13 +163,14 @@ void plan_matrices(const muon_param* p, int n, int ns_dtype, std::vector<MatPlan
     q.n = (int)std::max(q.rows, q.cols);
     q.w_dtype = p[i].w_dtype;
     q.g_dtype = p[i].g_dtype;
-    q.tile = ns_dtype == MUON_BF16 ? kShapeTile[kShape128] : kF32Tile;
+    q.tile = on_matrix_cores(ns_dtype) ? kShapeTile[kShape128] : kF32Tile;
     q.mp = round_up_i(q.m, q.tile);
     q.np = round_up_i(q.n, q.tile);
     const int ap = q.transposed ? q.np : q.mp, bp = q.transposed ? q.mp : q.np;
     q.ew_tr = ap / kEwTile;
     q.ew_tc = bp / kEwTile;
-    q.ns_bytes = align_up(es * (size_t)q.mp * q.np, 256) * x_buffers(q, ns_dtype) + align_up(es * (size_t)q.mp * q.mp, 256) * 2;
+    q.ns_bytes = (align_up(es * (size_t)q.mp * q.np, 256) * x_buffers(q, ns_dtype) + align_up(es * (size_t)q.mp * q.mp, 256) * 2) *
+                 (size_t)planes_of(ns_dtype);
     q.part_off = total_partials;
     total_partials += (size_t)q.ew_tr * q.ew_tc;
     q.chunk = 0;
@@ -363,7 +370,8 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
   const size_t off_part = off; off += tl.partials;
   size_t cursor = off;   // ew tiles and gemm tables are appended from here
   unsigned char* ns_base = ctx->ws + tl.total;
-  const size_t es = ns_dtype == MUON_BF16 ? 2 : 4;
+  const size_t es = on_matrix_cores(ns_dtype) ? 2 : 4;
+  const size_t planes = (size_t)planes_of(ns_dtype);
 
   MatDesc* h_mats = reinterpret_cast<MatDesc*>(img.data() + off_mats);
   auto dev = [&](size_t o) { return ctx->ws + o; };
@@ -374,12 +382,14 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
       const MatPlan& q = ctx->mats[i];
       MatDesc& d = h_mats[i];
       const size_t xb = align_up(es * (size_t)q.mp * q.np, 256), ab = align_up(es * (size_t)q.mp * q.mp, 256);
-      d.X = ns_base + ns_off; ns_off += xb;
-      d.Xt[0] = ns_base + ns_off; ns_off += xb;
+      d.X = ns_base + ns_off; ns_off += xb * planes;
+      d.Xt[0] = ns_base + ns_off; ns_off += xb * planes;
       d.Xt[1] = nullptr;
-      if (x_buffers(q, ns_dtype) == 3) { d.Xt[1] = ns_base + ns_off; ns_off += xb; }
-      d.Ag = ns_base + ns_off; ns_off += ab;
-      d.Bp = ns_base + ns_off; ns_off += ab;
+      if (x_buffers(q, ns_dtype) == 3) { d.Xt[1] = ns_base + ns_off; ns_off += xb * planes; }
+      d.Ag = ns_base + ns_off; ns_off += ab * planes;
+      d.Bp = ns_base + ns_off; ns_off += ab * planes;
+      d.x_plane = planes > 1 ? (int64_t)(xb / es) : 0;
+      d.pad_ = 0;
       d.partials = reinterpret_cast<float*>(dev(off_part)) + q.part_off;
       d.scal = reinterpret_cast<float*>(dev(off_scal)) + 4 * (size_t)i;
       d.rows = (int)q.rows; d.cols = (int)q.cols;
@@ -437,7 +447,9 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         const MatDesc& d = h_mats[members[k]];
         GemmProblem gp{};
         gp.scal = d.scal;
-        const bool bf = ns_dtype == MUON_BF16;
+        const bool bf = on_matrix_cores(ns_dtype);
+        const size_t xb = align_up(es * (size_t)q.mp * q.np, 256), ab = align_up(es * (size_t)q.mp * q.mp, 256);
+        const int64_t xpl = planes > 1 ? (int64_t)(xb / es) : 0, apl = planes > 1 ? (int64_t)(ab / es) : 0;
         // bf16 path: ONE layout of the iterate, ping-ponging between X and Xt[0] (both m_pad x n_pad); fp32 path: X
         // updated in place plus its transpose ping-ponging between Xt[0] and Xt[1].
         void* const xbuf[2] = {d.X, bf ? d.Xt[0] : d.X};
@@ -445,11 +457,13 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         for (int par = 0; par < 2; ++par) {
           gp.L = xbuf[par]; gp.R = xbuf[par]; gp.E = nullptr; gp.Et = nullptr; gp.C = d.Ag; gp.Ct = nullptr;
           gp.K = q.np; gp.ldl = q.np; gp.ldr = q.np; gp.lde = 0; gp.ldet = 0; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+          gp.l_plane = xpl; gp.r_plane = xpl; gp.et_plane = 0; gp.c_plane = apl; gp.ct_plane = apl;
           reinterpret_cast<GemmProblem*>(img.data() + g.prob_gram[par])[k] = gp;
         }
         // polynomial: B = b A + c A A  (A is symmetric, so it is its own transposed addend)
         gp.L = d.Ag; gp.R = d.Ag; gp.E = d.Ag; gp.Et = d.Ag; gp.C = d.Bp; gp.Ct = nullptr;
         gp.K = q.mp; gp.ldl = q.mp; gp.ldr = q.mp; gp.lde = q.mp; gp.ldet = q.mp; gp.ldc = q.mp; gp.ldct = q.mp; gp.symmetric = 1;
+        gp.l_plane = apl; gp.r_plane = apl; gp.et_plane = apl; gp.c_plane = apl; gp.ct_plane = apl;
         gp.diag_add = folds_identity(q, ns_dtype) ? 1 : 0;
         reinterpret_cast<GemmProblem*>(img.data() + g.prob_poly)[k] = gp;
         gp.diag_add = 0;
@@ -466,6 +480,7 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
               gp.Et = folds_identity(q, ns_dtype) ? nullptr : xbuf[par]; gp.ldet = q.np;
               gp.C = nullptr; gp.ldc = 0; gp.Ct = xbuf[par ^ 1]; gp.ldct = q.np;
               if (last && q.transposed) { gp.C = d.Xt[1]; gp.ldc = q.mp; gp.Ct = nullptr; gp.ldct = 0; }
+              gp.l_plane = xpl; gp.r_plane = apl; gp.et_plane = xpl; gp.c_plane = xpl; gp.ct_plane = xpl;
             } else {
               // apply, fp32: X' = a X + B X, reading X^T from Xt[p], writing X in place and X'^T to Xt[p^1]; the last
               // iteration writes only the layout W needs.
@@ -481,22 +496,22 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
       }
       // tile tables: level 1 = whole 256-tiles (bf16 only), level 0 = what they leave uncovered
       for (int level = 1; level >= 0; --level) {
-        if (level == 1 && ns_dtype != MUON_BF16) continue;
+        if (level == 1 && !on_matrix_cores(ns_dtype)) continue;
         std::vector<std::vector<GemmTile>> sym(members.size()), app(members.size()), app_last(members.size());
         size_t n_sym = 0, n_app = 0, n_last = 0;
         for (size_t k = 0; k < members.size(); ++k) {
           const MatPlan& q = ctx->mats[members[k]];
-          const int cm = ns_dtype == MUON_BF16 ? q.mp / kCoarse : 0, cn = ns_dtype == MUON_BF16 ? q.np / kCoarse : 0;
+          const int cm = on_matrix_cores(ns_dtype) ? q.mp / kCoarse : 0, cn = on_matrix_cores(ns_dtype) ? q.np / kCoarse : 0;
           if (level == 1) {
             blocked_tiles((int32_t)k, cm, cm, true, 0, 0, sym[k]);
             // tiles of X'^T; 8 x 4 blocks measured 1 % faster than 4 x 8 here (the K-major panels are the strided ones)
-            if (ns_dtype == MUON_BF16) blocked_tiles((int32_t)k, cn, cm, false, 0, 0, app[k], 8, 4);
+            if (on_matrix_cores(ns_dtype)) blocked_tiles((int32_t)k, cn, cm, false, 0, 0, app[k], 8, 4);
             else blocked_tiles((int32_t)k, cm, cn, false, 0, 0, app[k]);
             app_last[k] = app[k];
           } else {
             const int tm = q.mp / q.tile, tn = q.np / q.tile, r = kCoarse / q.tile;
             blocked_tiles((int32_t)k, tm, tm, true, cm * r, cm * r, sym[k]);
-            if (ns_dtype == MUON_BF16) blocked_tiles((int32_t)k, tn, tm, false, cn * r, cm * r, app[k], 8, 4);
+            if (on_matrix_cores(ns_dtype)) blocked_tiles((int32_t)k, tn, tm, false, cn * r, cm * r, app[k], 8, 4);
             else blocked_tiles((int32_t)k, tm, tn, false, cm * r, cn * r, app[k]);
             app_last[k] = app[k];
           }
@@ -574,11 +589,12 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
 
   const int N = hp->ns_steps;
   const int use_s = N == 0;
-  const bool bf16_path = ctx->ns_dtype == MUON_BF16;
+  const bool bf16_path = on_matrix_cores(ctx->ns_dtype);
+  const int planes = planes_of(ctx->ns_dtype);
   // where O ends up (see o_source in the elementwise kernels): fp32 path: X in place, its transpose in Xt[N & 1];
   // bf16 path: X ping-pong index N & 1 (bit 1), transposed matrices in Xt[1], or Xt[0] when no iteration ran (bit 0)
   const int o_sel = bf16_path ? ((N & 1) << 1) | (N > 0 ? 1 : 0) : (N & 1);
-  const bool bf = ctx->ns_dtype == MUON_BF16;
+  const bool bf = bf16_path;
   if (hp->coeff_schedule)
     for (int i = 0; i < 3 * N; ++i)
       if (!std::isfinite(hp->coeff_schedule[i])) return MUON_E_INVALID_ARG;
@@ -602,7 +618,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           if (ts.n_sym == 0) continue;
           if (bf)
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f,
-                                                        first ? 1 : -1, 0.f, 0, s));
+                                                        first ? 1 : -1, 0.f, 0, planes, s));
           else
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f, first ? 1 : -1, s));
         }
@@ -610,7 +626,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
           if (bf)
-            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, 0, s));
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, 0, planes, s));
           else
             MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
         }
@@ -621,7 +637,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           if (n_app == 0) continue;
           if (bf)
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_apply[par * 2 + last]), T(t_app),
-                                                              n_app, 1.f, a, first ? 0 : -1, 0.f, 1, s));
+                                                              n_app, 1.f, a, first ? 0 : -1, 0.f, 1, planes, s));
           else
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(t_app), n_app, 1.f, a,
                                                              first ? 0 : -1, s));
@@ -657,7 +673,7 @@ int muon_debug_read_update(muon_ctx* ctx, int32_t index, void* dst, int32_t dst_
 int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t cap) {
   if (!ctx || !out || index < 0 || index >= ctx->n || cap < 0) return MUON_E_INVALID_ARG;
   const MatPlan& q = ctx->mats[index];
-  const int coarse = ctx->ns_dtype == MUON_BF16 && q.mp >= kCoarse ? kCoarse : q.tile;
+  const int coarse = on_matrix_cores(ctx->ns_dtype) && q.mp >= kCoarse ? kCoarse : q.tile;
   const int64_t v[8] = {q.m, q.n, q.transposed, q.mp, q.np, q.chunk, coarse, q.tile};
   const int k = std::min<int>(cap, 8);
   for (int i = 0; i < k; ++i) out[i] = v[i];

@@ -25,8 +25,10 @@ hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, 
 // a4-a6: grouped NT GEMM with fused epilogue.  alpha_idx: -1 none, 0 -> scal[0], 1 -> scal[1].  diag_add: constant
 // added to the diagonal of the outputs of problems that ask for it (GemmProblem::diag_add), bf16 kernel only.
 // l_kmajor: every problem of the launch stores its L operand K-major (element (i, k) at L[k * ldl + i]).
+// planes: 1 = plain bf16; 2 or 3 = every matrix is a sum of that many bf16 planes (GemmProblem::*_plane strides).
 hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
-                            float beta_acc, float beta_e, int alpha_idx, float diag_add, int l_kmajor, hipStream_t s);
+                            float beta_acc, float beta_e, int alpha_idx, float diag_add, int l_kmajor, int planes,
+                            hipStream_t s);
 hipError_t launch_gemm_f32(const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
                            float beta_acc, float beta_e, int alpha_idx, hipStream_t s);
 

@@ -8,6 +8,8 @@ namespace muon {
 constexpr int kEwTile = 64;        // elementwise kernels work on 64x64 element tiles
 constexpr int kDtypeF32 = 0;
 constexpr int kDtypeBF16 = 1;
+constexpr int kDtypeBF16X2 = 2;    // Newton-Schulz storage only: sum of two bf16 planes
+constexpr int kDtypeBF16X3 = 3;    // Newton-Schulz storage only: sum of three bf16 planes
 
 // Static per-matrix record (built once at init).
 struct MatDesc {
@@ -28,6 +30,8 @@ struct MatDesc {
   int32_t n_part;     // number of partials
   int32_t ew_tiles_c; // 64-wide tile columns in U's orientation (padded)
   float sqrt_max;     // sqrt(max(A, B))
+  int32_t pad_;
+  int64_t x_plane;    // split-bf16 path: elements from one bf16 plane of X / Xt[] to the next (0 otherwise)
 };
 
 // Per-step pointers (re-uploaded only when they change).
@@ -63,6 +67,8 @@ struct GemmProblem {
   int32_t ldl, ldr, lde, ldet, ldc, ldct;
   int32_t symmetric;  // output is symmetric: off-diagonal tiles are also stored mirrored into C
   int32_t diag_add;   // square output only: add the launch's diagonal constant to C[i][i] before rounding
+  // split-bf16 launches (every matrix = sum of several bf16 planes): elements from one plane to the next
+  int64_t l_plane, r_plane, et_plane, c_plane, ct_plane;
 };
 
 struct GemmTile {

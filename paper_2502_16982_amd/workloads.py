@@ -39,7 +39,7 @@ class Workload:
     shapes: Tuple[Tuple[int, int], ...]      # (A, B) per matrix, in list order
     w_dtype: torch.dtype
     g_dtype: torch.dtype
-    ns_dtype: str                             # "bf16" or "f32"
+    ns_dtype: str                             # "bf16", "f32", "bf16x2" or "bf16x3"
     w_std: float
     g_std: float
     outlier_frac: float = 0.0

@@ -10,6 +10,9 @@ from paper_2502_16982_amd import binding, workloads
 
 TOL_F32_FRO = 1e-4      # relative Frobenius error of O, fp32 Newton-Schulz path
 TOL_BF16_FRO = 2e-2     # relative Frobenius error of O, bf16 Newton-Schulz path
+# split-bf16 paths: the fp32 path's bar for two planes (each product is good to about 2^-16), a tighter one for three
+# planes (what is left is the fp32 accumulation and the fp32 epilogue arithmetic)
+TOL_SPLIT_FRO = {"bf16x2": 1e-4, "bf16x3": 1e-5}
 TOL_ELEM = 1e-6         # elementwise momentum / update error relative to the sum of term magnitudes
 
 
@@ -74,10 +77,14 @@ def check_weight_update(w_gpu: torch.Tensor, w0: np.ndarray, o_gpu: np.ndarray, 
     if w_gpu.dtype == torch.float32:
         err = np.abs(got - ref) / np.maximum(scale, 1e-300)
         return {"max_rel": float(err.max()), "frac_off": 0.0}
+    # bf16 weights: the library rounds an fp32 value v once (to nearest even), and v is within the fp32 forward error
+    # TOL_ELEM * scale of the exact result, so |got - exact| <= ulp/2 + TOL_ELEM * scale, with the ulp of the binade
+    # the rounding lands in.  The second term only matters where the update cancels most of the weight.  Against the
+    # fp64 result rounded to bf16 the library may therefore differ, by one ulp, on a small fraction (double rounding).
     ref_b = bf16_round(ref)
-    diff = np.abs(got - ref_b)
-    ulp = bf16_ulp(ref)
-    return {"max_ulp": float((diff / ulp).max()), "frac_off": float(np.mean(diff > 0))}
+    bound = 0.5 * np.maximum(bf16_ulp(ref), bf16_ulp(got)) + TOL_ELEM * scale
+    return {"max_excess": float((np.abs(got - ref) / np.maximum(bound, 1e-300)).max()),
+            "frac_off": float(np.mean(np.abs(got - ref_b) > 0))}
 
 
 def run_and_compare(wl: workloads.Workload, device, check=None, steps: int = 1, hp_over=None, max_ws: int = 0,

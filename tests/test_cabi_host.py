@@ -65,6 +65,9 @@ def test_workspace_bytes_validation(binding):
     assert L.muon_workspace_bytes(p, 0, 1, 0, C.byref(out)) == -1
     assert L.muon_workspace_bytes(p, 1, 1, 0, None) == -1
     assert L.muon_workspace_bytes(p, 1, 7, 0, C.byref(out)) == -2
+    assert L.muon_workspace_bytes(p, 1, 4, 0, C.byref(out)) == -2
+    bad = binding.param_array([(8, 8)], [binding.MUON_BF16X2], [0])      # the split forms are no buffer dtypes
+    assert L.muon_workspace_bytes(bad, 1, 1, 0, C.byref(out)) == -2
     bad = binding.param_array([(0, 256)], [0], [0])
     assert L.muon_workspace_bytes(bad, 1, 1, 0, C.byref(out)) == -1
     bad = binding.param_array([(8, 8)], [5], [0])
@@ -86,6 +89,10 @@ def test_workspace_bytes_scale_with_dtype_and_cap(binding):
     assert f32 >= 4 * elems32 and f32 < 4 * elems32 * 1.2 + (1 << 22)
     capped = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16, max_bytes=bf // 3)
     assert capped < bf and capped % 256 == 0
+    # the split forms keep two / three bf16 planes of every temporary
+    for planes, code in ((2, binding.MUON_BF16X2), (3, binding.MUON_BF16X3)):
+        sp = binding.muon_workspace_bytes(p, 6, code)
+        assert sp >= planes * 2 * elems16 and sp < planes * 2 * elems16 * 1.2 + (1 << 22)
     tiny = binding.muon_workspace_bytes(p, 6, binding.MUON_BF16, max_bytes=1)
     one = 2 * (3 * 1024 * 4096 + 2 * 1024 * 1024)     # the largest single matrix is the transposed 4096 x 1024
     assert one <= tiny < one + (1 << 22)
