@@ -1,5 +1,7 @@
 """GPU parity at the benchmark's full sizes: each workload is stepped whole, in the launch configuration
 the bench times, and sampled matrices (one per distinct shape) are checked against the fp64 oracle."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -46,6 +48,21 @@ def test_block_w4096_full(dev):
     # 4096x4096 and 11008x4096 (transposed orientation) are checked elementwise against the oracle;
     # the 4096x11008 matrices are covered by invariants below (their oracle run alone takes a minute)
     assert_records(U.run_and_compare(wl, dev, check=[0, 6]), U.TOL_BF16_FRO)
+
+
+@pytest.mark.timeout(600)
+def test_block_w4096_full_two_planes(dev):
+    """The accurate matrix-core path at the benchmark's sizes and launch configuration: the whole block is stepped
+    with two bf16 planes per temporary; one 4096 x 4096 matrix and the 11008 x 4096 one against the oracle."""
+    wl = dataclasses.replace(workloads.workload("block_w4096"), ns_dtype="bf16x2")
+    assert_records(U.run_and_compare(wl, dev, check=[0, 6]), U.TOL_SPLIT_FRO["bf16x2"])
+
+
+@pytest.mark.parametrize("ns", ["bf16x2", "bf16x3"])
+def test_moe_expert_shapes_split(dev, ns):
+    """One expert's three matrices at their real shape (m = 1408: 256-tiles plus 128-wide strips, both orientations)."""
+    wl = workloads.custom("expert_" + ns, [(2048, 1408), (2048, 1408), (1408, 2048)], ns_dtype=ns, seed_base=4100)
+    assert_records(U.run_and_compare(wl, dev), U.TOL_SPLIT_FRO[ns])
 
 
 def test_block_w4096_invariants(dev):
