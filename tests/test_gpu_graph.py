@@ -14,6 +14,9 @@ pytestmark = pytest.mark.gpu
 CASES = {
     "bf16_mixed": dict(shapes=[(128, 256), (384, 256), (200, 136), (256, 640)], ns_dtype="bf16",
                        w_dtype=torch.bfloat16, g_dtype=torch.bfloat16),
+    # two bf16 planes; the 256 x 256 instantiations of this path use per-lane scratch memory in their epilogue
+    "bf16x2_mixed": dict(shapes=[(512, 640), (384, 256), (200, 136)], ns_dtype="bf16x2",
+                         w_dtype=torch.bfloat16, g_dtype=torch.bfloat16),
     "f32_single": dict(shapes=[(128, 256)], ns_dtype="f32", w_dtype=torch.float32, g_dtype=torch.float32),
 }
 
