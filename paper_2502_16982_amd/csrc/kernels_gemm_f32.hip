@@ -27,11 +27,16 @@ __global__ __launch_bounds__(256) void ns_gemm_f32_kernel(const GemmProblem* __r
   const float* lptr = static_cast<const float*>(p.L) + (size_t)(row0 + ld_row) * p.ldl + ld_k4;
   const float* rptr = static_cast<const float*>(p.R) + (size_t)(col0 + ld_row) * p.ldr + ld_k4;
 
-  float acc[4][4];
+  // Two-level accumulation: `acc` takes at most kFlush slabs (1024 terms) before it is added to `total`, so the
+  // rounding error of a dot product grows with K / 1024 + 1024 terms instead of K (a single fp32 accumulator over
+  // 2^20 squares drifts by 4e-4 relative).
+  constexpr int kFlush = 64;
+  float acc[4][4], total[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+    for (int j = 0; j < 4; ++j) acc[i][j] = total[i][j] = 0.f;
+  int since = 0;
 
   for (int k0 = 0; k0 < p.K; k0 += KS) {
     const float4 lv = *reinterpret_cast<const float4*>(lptr + k0);
@@ -51,7 +56,21 @@ __global__ __launch_bounds__(256) void ns_gemm_f32_kernel(const GemmProblem* __r
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
     }
+    if (++since == kFlush) {
+      since = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          total[i][j] += acc[i][j];
+          acc[i][j] = 0.f;
+        }
+    }
   }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) total[i][j] += acc[i][j];
 
   const float alpha = alpha_idx >= 0 ? p.scal[alpha_idx] : 1.f;
   const float* E = static_cast<const float*>(p.E);
@@ -68,7 +87,7 @@ __global__ __launch_bounds__(256) void ns_gemm_f32_kernel(const GemmProblem* __r
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int c = col0 + tx * 4 + j;
-      float x = beta_acc * acc[i][j];
+      float x = beta_acc * total[i][j];
       if (E) x = fmaf(beta_e, E[(size_t)r * p.lde + c], x);
       x *= alpha;
       if (C) C[(size_t)r * p.ldc + c] = x;

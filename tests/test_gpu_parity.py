@@ -261,6 +261,52 @@ def test_zero_gradient_only_decays(dev):
         st.close()
 
 
+@pytest.mark.parametrize("ns", ["bf16", "bf16x2", "f32"])
+def test_extreme_aspect_ratios(dev, ns):
+    """One-row / one-column matrices and a 130 x 33000 one: iterates that are almost all padding, K loops of 500+ slabs."""
+    tol = {"bf16": U.TOL_BF16_FRO, "bf16x2": U.TOL_SPLIT_FRO["bf16x2"], "f32": U.TOL_F32_FRO}[ns]
+    wl = workloads.custom("extreme_" + ns, [(1, 70000), (70000, 1), (130, 33000)], ns_dtype=ns, seed_base=61)
+    assert_records(U.run_and_compare(wl, dev, steps=2), tol)
+
+
+@pytest.mark.parametrize("ns", ["bf16", "bf16x2", "f32"])
+def test_largest_dimensions(dev, ns):
+    """The largest row / column counts the interface accepts (2^20), both orientations: tile indices at the top of their
+    range, K loops of 16384 slabs.  Gaussian gradient except for three 64-wide bands (first, middle and last K slab of
+    the Gram product) scaled by 128, each carrying as much energy as all the rest, so that a slab dropped or read twice
+    where a boundary could go wrong moves O by tens of percent.  Four equal singular values make the relative error of
+    O that of ONE number, which the five iterations amplify about 5 times (nothing averages out): the bars are widened
+    to 1e-1 (bf16; an emulation of ideal bf16 storage on Gaussian 4 x 2^20 gives 3e-2) and 3e-4 (two planes; emulation
+    5e-5, measured 0.8-1.1e-4); the fp32 path keeps 1e-4.  (Inputs with only a few distinct values are another matter
+    at this length: a matrix-core accumulator is one chain of K / 16 fp32 additions whose rounding errors then all
+    point the same way - 1e-2 in O for a +-2^-10 sign matrix with two or three planes alike.)"""
+    big = 1 << 20
+    tol = {"bf16": 1e-1, "bf16x2": 3e-4, "f32": U.TOL_F32_FRO}[ns]
+    for shape in ((4, big), (big, 4)):
+        gen = torch.Generator(device=dev).manual_seed(62 + shape[0] % 7)
+        g = torch.randn(shape, generator=gen, device=dev) * 1e-3
+        gl = g if shape[1] == big else g.t()
+        for start in (0, big // 2 - 64, big - 64):
+            gl[:, start:start + 64] *= 128.0
+        g = g.to(torch.bfloat16)
+        w = (torch.randn(shape, generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+        m = torch.zeros(shape, device=dev)
+        w0, g0 = U.to64(w), U.to64(g)
+        hp, d = U.hp_from(workloads.Hyper(), lr=0.02, weight_decay=0.1)
+        st = binding.MuonStepper([(w, g, m)], ns_dtype=ns)
+        st.step(hp)
+        torch.cuda.synchronize()
+        W, M, O = U.oracle_step(w0, g0, np.zeros(shape), d)
+        o_gpu = U.to64(st.read_update(0))
+        err = U.rel_fro(o_gpu, O)
+        print({"ns": ns, "shape": shape, "o_rel_fro": err}, flush=True)
+        assert torch.equal(m, g.float())
+        assert err <= tol, (shape, err)
+        chk = U.check_weight_update(w, w0, o_gpu, d)
+        assert chk["max_excess"] <= 1.0 and chk["frac_off"] <= 2e-3, chk
+        st.close()
+
+
 def test_lr_zero_leaves_weights_bitwise(dev):
     wl = workloads.custom("lr0", [(100, 300)], seed_base=31)
     (w, g, m), = workloads.make_all(wl, dev)
