@@ -9,6 +9,9 @@
 //     apply      T  = X'^T = X^T B'        L = X read K-major, R = B'  (stores T^T = X' row-major; T itself only
 //                                                                       where O is wanted transposed)
 // Operands are zero-padded to whole tiles by the producer, so the kernel has no edge handling.
+// The same kernel also runs the split-bf16 forms (template parameter PL, see seg_count below): every matrix a sum of
+// 2 or 3 bf16 planes, each product one K loop over the plane pairs that matter, the epilogue splitting the fp32
+// result into planes again.
 //
 // Design for CDNA4:
 //  * v_mfma_f32_32x32x16_bf16 (the 16x16x32 form runs at half the rate on this chip), wave tile = FM x FN

@@ -447,12 +447,12 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         const MatDesc& d = h_mats[members[k]];
         GemmProblem gp{};
         gp.scal = d.scal;
-        const bool bf = on_matrix_cores(ns_dtype);
+        const bool mc = on_matrix_cores(ns_dtype);
         const size_t xb = align_up(es * (size_t)q.mp * q.np, 256), ab = align_up(es * (size_t)q.mp * q.mp, 256);
         const int64_t xpl = planes > 1 ? (int64_t)(xb / es) : 0, apl = planes > 1 ? (int64_t)(ab / es) : 0;
         // bf16 path: ONE layout of the iterate, ping-ponging between X and Xt[0] (both m_pad x n_pad); fp32 path: X
         // updated in place plus its transpose ping-ponging between Xt[0] and Xt[1].
-        void* const xbuf[2] = {d.X, bf ? d.Xt[0] : d.X};
+        void* const xbuf[2] = {d.X, mc ? d.Xt[0] : d.X};
         // Gram: A = X X^T
         for (int par = 0; par < 2; ++par) {
           gp.L = xbuf[par]; gp.R = xbuf[par]; gp.E = nullptr; gp.Et = nullptr; gp.C = d.Ag; gp.Ct = nullptr;
@@ -470,7 +470,7 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
         for (int par = 0; par < 2; ++par)
           for (int last = 0; last < 2; ++last) {
             gp.symmetric = 0;
-            if (bf) {
+            if (mc) {
               // apply, bf16: the product is posed transposed, T = X'^T = X^T B, with its L operand X^T read K-major
               // straight from the row-major X; the kernel's cheap transposed store of T is then X' itself, row-major.
               // Only the last iteration of a matrix iterated on its transpose needs T as it is (O in W's
@@ -589,12 +589,11 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
 
   const int N = hp->ns_steps;
   const int use_s = N == 0;
-  const bool bf16_path = on_matrix_cores(ctx->ns_dtype);
+  const bool mc = on_matrix_cores(ctx->ns_dtype);   // bf16 or split-bf16: the MFMA kernels and their one-layout plan
   const int planes = planes_of(ctx->ns_dtype);
   // where O ends up (see o_source in the elementwise kernels): fp32 path: X in place, its transpose in Xt[N & 1];
   // bf16 path: X ping-pong index N & 1 (bit 1), transposed matrices in Xt[1], or Xt[0] when no iteration ran (bit 0)
-  const int o_sel = bf16_path ? ((N & 1) << 1) | (N > 0 ? 1 : 0) : (N & 1);
-  const bool bf = bf16_path;
+  const int o_sel = mc ? ((N & 1) << 1) | (N > 0 ? 1 : 0) : (N & 1);
   if (hp->coeff_schedule)
     for (int i = 0; i < 3 * N; ++i)
       if (!std::isfinite(hp->coeff_schedule[i])) return MUON_E_INVALID_ARG;
@@ -603,7 +602,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
     const Chunk& ch = ctx->chunks[ci];
     const EwTile* ew = reinterpret_cast<const EwTile*>(ctx->ws + ch.ew_tiles_off);
     MUON_TIMED(MUON_PROF_MOMENTUM, launch_momentum_norm_cast(ctx->d_mats, ctx->d_ptrs, ew, ch.n_ew_tiles, (float)hp->momentum,
-                                                             hp->nesterov != 0, (!bf16_path || N == 0) ? 1 : 0, ctx->ns_dtype, s));
+                                                             hp->nesterov != 0, (!mc || N == 0) ? 1 : 0, ctx->ns_dtype, s));
     MUON_TIMED(MUON_PROF_NORM, launch_norm_finalize(ctx->d_mats, ch.first, ch.count, hp->eps, s));
     for (int it = 0; it < N; ++it) {
       const int first = it == 0, last = it == N - 1, par = it & 1;
@@ -616,7 +615,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
         for (int level = 1; level >= 0; --level) {
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
-          if (bf)
+          if (mc)
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f,
                                                         first ? 1 : -1, 0.f, 0, planes, s));
           else
@@ -625,7 +624,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
         for (int level = 1; level >= 0; --level) {
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
-          if (bf)
+          if (mc)
             MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, 0, planes, s));
           else
             MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
@@ -635,7 +634,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
           const size_t t_app = last ? ts.apply_last : ts.apply;
           const int n_app = last ? ts.n_apply_last : ts.n_apply;
           if (n_app == 0) continue;
-          if (bf)
+          if (mc)
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level ? kShape256 : kShape128, P(g.prob_apply[par * 2 + last]), T(t_app),
                                                               n_app, 1.f, a, first ? 0 : -1, 0.f, 1, planes, s));
           else
