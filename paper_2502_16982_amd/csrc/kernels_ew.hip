@@ -21,6 +21,7 @@ __device__ __forceinline__ u16 f32_to_bf16(float f) {
   return (u16)(u >> 16);
 }
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
@@ -265,51 +266,126 @@ __device__ __forceinline__ const void* o_source(const MatDesc& d, int o_sel) {
   return (o_sel & 2) ? d.Xt[0] : d.X;
 }
 
+// 8 consecutive elements: one 16-byte access for bf16, two for fp32
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float* out);
+template <>
+__device__ __forceinline__ void load8<float>(const float* p, float* out) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float4 v = reinterpret_cast<const float4*>(p)[i];
+    out[4 * i + 0] = v.x; out[4 * i + 1] = v.y; out[4 * i + 2] = v.z; out[4 * i + 3] = v.w;
+  }
+}
+template <>
+__device__ __forceinline__ void load8<u16>(const u16* p, float* out) {
+  // streaming hint: every element of the update is touched once; without it the L2 refetched a third of the lines
+  // (measured: 1.20 GB fetched for 0.81 GB of W and O on the 4096-wide block, 0.89 GB with the hint)
+  const u32x4_t vv = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  const uint4 v = make_uint4(vv.x, vv.y, vv.z, vv.w);
+  const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    out[2 * j] = __uint_as_float(w[j] << 16);
+    out[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+  }
+}
+template <typename T>
+__device__ __forceinline__ void store8(T* p, const float* in);
+template <>
+__device__ __forceinline__ void store8<float>(float* p, const float* in) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    reinterpret_cast<float4*>(p)[i] = make_float4(in[4 * i], in[4 * i + 1], in[4 * i + 2], in[4 * i + 3]);
+}
+template <>
+__device__ __forceinline__ void store8<u16>(u16* p, const float* in) {
+  const u32x4_t vv = {pack2(in[0], in[1]), pack2(in[2], in[3]), pack2(in[4], in[5]), pack2(in[6], in[7])};
+  __builtin_nontemporal_store(vv, reinterpret_cast<u32x4_t*>(p));
+}
+template <typename XT, int PL>
+__device__ __forceinline__ void ns_load8(const XT* p, size_t plane, float* out) {
+  load8<XT>(p + (PL - 1) * plane, out);
+  if constexpr (PL > 1) {
+#pragma unroll
+    for (int q = PL - 2; q >= 0; --q) {        // smallest plane first
+      float v[8];
+      load8<XT>(p + q * plane, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] += v[i];
+    }
+  }
+}
+
+// One 64x64 tile of the update.  Thread t owns 8 consecutive columns, (t % 8) * 8 .., of rows t / 8 and t / 8 + 32:
+// the 8 lanes that share a row cover one whole 128-byte line of a bf16 array with every load or store instruction
+// (a thread that owned 16 consecutive elements wrote every line in two instructions of scattered 16-byte pieces).
 template <typename WT, typename XT, int PL, bool UPDATE>
 __device__ __forceinline__ void apply_tile(const MatDesc& d, const MatPtrs& pt, int tr, int tc, float lr, float wd,
                                            float scale, int o_sel, float* red) {
   const int tid = threadIdx.x;
-  const int r = tr * kEwTile + (tid >> 2);
-  const int c0 = tc * kEwTile + (tid & 3) * 16;
+  const int c0 = tc * kEwTile + (tid & 7) * 8;
   const int A = d.rows, B = d.cols;
   WT* w = static_cast<WT*>(pt.w);
   const XT* o = static_cast<const XT*>(o_source(d, o_sel));
   const int pitch = d.transposed ? d.mp : d.np;
   const size_t plane = (size_t)d.x_plane;
+  const int r0 = tr * kEwTile + (tid >> 3), r1 = r0 + 32;
   float ss = 0.f;
-  if (r < A && c0 < B) {
-    const size_t base = (size_t)r * (size_t)B + (size_t)c0;
-    const XT* op = o + (size_t)r * pitch + c0;
-    if (!UPDATE) {
-      if (c0 + 16 <= B) {
-        float ov[16];
-        ns_load16<XT, PL>(op, plane, ov);
+  const bool wide = (c0 + 8 <= B) && ((B & 7) == 0) && (!UPDATE || aligned16(w));
+  if (wide && r1 < A) {
+    // both rows at once: all loads are issued before the first store
+    float ov[2][8], wv[2][8];
+    ns_load8<XT, PL>(o + (size_t)r0 * pitch + c0, plane, ov[0]);
+    ns_load8<XT, PL>(o + (size_t)r1 * pitch + c0, plane, ov[1]);
+    if (UPDATE) {
+      load8<WT>(w + (size_t)r0 * (size_t)B + c0, wv[0]);
+      load8<WT>(w + (size_t)r1 * (size_t)B + c0, wv[1]);
+    }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) ss = fmaf(ov[i], ov[i], ss);
-      } else {
-        for (int i = 0; i < 16 && c0 + i < B; ++i) {
-          const float ov = ns_load1<XT, PL>(op + i, plane);
-          ss = fmaf(ov, ov, ss);
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        ss = fmaf(ov[u][i], ov[u][i], ss);
+        if (UPDATE) {
+          const float t = fmaf(wd, wv[u][i], scale * ov[u][i]);
+          wv[u][i] = fmaf(-lr, t, wv[u][i]);
         }
       }
-    } else if ((c0 + 16 <= B) && ((B & 7) == 0) && aligned16(w)) {
-      float wv[16], ov[16];
-      load16<WT>(w + base, wv);
-      ns_load16<XT, PL>(op, plane, ov);
+    if (UPDATE) {
+      store8<WT>(w + (size_t)r0 * (size_t)B + c0, wv[0]);
+      store8<WT>(w + (size_t)r1 * (size_t)B + c0, wv[1]);
+    }
+  } else {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        ss = fmaf(ov[i], ov[i], ss);
-        const float t = fmaf(wd, wv[i], scale * ov[i]);
-        wv[i] = fmaf(-lr, t, wv[i]);
-      }
-      store16<WT>(w + base, wv);
-    } else {
-      for (int i = 0; i < 16 && c0 + i < B; ++i) {
-        const float ov = ns_load1<XT, PL>(op + i, plane);
-        const float wv = load1<WT>(w + base + i);
-        ss = fmaf(ov, ov, ss);
-        const float t = fmaf(wd, wv, scale * ov);
-        store1<WT>(w + base + i, fmaf(-lr, t, wv));
+    for (int u = 0; u < 2; ++u) {
+      const int r = u ? r1 : r0;
+      if (r >= A || c0 >= B) continue;
+      const size_t base = (size_t)r * (size_t)B + (size_t)c0;
+      const XT* op = o + (size_t)r * pitch + c0;
+      if (wide) {
+        float ov[8], wv[8];
+        ns_load8<XT, PL>(op, plane, ov);
+        if (UPDATE) load8<WT>(w + base, wv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          ss = fmaf(ov[i], ov[i], ss);
+          if (UPDATE) {
+            const float t = fmaf(wd, wv[i], scale * ov[i]);
+            wv[i] = fmaf(-lr, t, wv[i]);
+          }
+        }
+        if (UPDATE) store8<WT>(w + base, wv);
+      } else {
+        for (int i = 0; i < 8 && c0 + i < B; ++i) {
+          const float ov = ns_load1<XT, PL>(op + i, plane);
+          ss = fmaf(ov, ov, ss);
+          if (UPDATE) {
+            const float wv = load1<WT>(w + base + i);
+            const float t = fmaf(wd, wv, scale * ov);
+            store1<WT>(w + base + i, fmaf(-lr, t, wv));
+          }
+        }
       }
     }
   }
