@@ -747,7 +747,30 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
         const int row = 16 * sx + 4 * fh + (t < 4 ? t : 4 + t);
         sel[sx][t] = (__bf16)(fr == row ? 1.0f : 0.0f);
       }
-#pragma unroll 1
+    // all planes at once, MFMA tile by MFMA tile: the fp32 values leave the accumulator registers for good
+    u32x2 pkq[PL][FM][FN][4];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+          float x0 = acc[i][j][4 * qq], x1 = acc[i][j][4 * qq + 1], x2 = acc[i][j][4 * qq + 2], x3 = acc[i][j][4 * qq + 3];
+#pragma unroll
+          for (int q = 0; q < PL; ++q) {
+            const u32x2 w = pack4(x0, x1, x2, x3);
+            pkq[q][i][j][qq] = w;
+            if (q + 1 < PL) {                    // what this plane left of the value
+              x0 -= __uint_as_float(w.x << 16);
+              x1 -= __uint_as_float(w.x & 0xffff0000u);
+              x2 -= __uint_as_float(w.y << 16);
+              x3 -= __uint_as_float(w.y & 0xffff0000u);
+            }
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
     for (int q = 0; q < PL; ++q) {
       if (Ct) {
         __syncthreads();                         // the image is free (addend consumed / previous plane stored)
@@ -756,11 +779,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
           for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int qq = 0; qq < 4; ++qq) {
-              *reinterpret_cast<u32x2*>(slot_of(i, j, qq)) =
-                  pack4(acc[i][j][4 * qq], acc[i][j][4 * qq + 1], acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]);
-              if (qq == 3) __builtin_amdgcn_sched_barrier(0);
-            }
+            for (int qq = 0; qq < 4; ++qq) *reinterpret_cast<u32x2*>(slot_of(i, j, qq)) = pkq[q][i][j][qq];
         __syncthreads();
         store_ct(Ct + (size_t)q * ctpl);
       }
@@ -775,9 +794,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
             for (int v = 0; v < 16; ++v) d[v] = 0.f;
 #pragma unroll
             for (int sx = 0; sx < 2; ++sx) {
-              const u32x2 w0 = pack4(acc[i][j][8 * sx], acc[i][j][8 * sx + 1], acc[i][j][8 * sx + 2], acc[i][j][8 * sx + 3]);
-              const u32x2 w1 = pack4(acc[i][j][8 * sx + 4], acc[i][j][8 * sx + 5], acc[i][j][8 * sx + 6], acc[i][j][8 * sx + 7]);
-              const u32x4 raw = {w0.x, w0.y, w1.x, w1.y};
+              const u32x4 raw = {pkq[q][i][j][2 * sx].x, pkq[q][i][j][2 * sx].y, pkq[q][i][j][2 * sx + 1].x, pkq[q][i][j][2 * sx + 1].y};
               d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), sel[sx], d, 0, 0, 0);
             }
             const int r = wm * WTM + i * 32 + fr;
@@ -791,21 +808,6 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
           }
         __syncthreads();
         store_c(C + (size_t)q * cpl);
-      }
-      if (q + 1 < PL) {                          // what this plane left of the value
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-          for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int qq = 0; qq < 4; ++qq) {
-              const u32x2 w = pack4(acc[i][j][4 * qq], acc[i][j][4 * qq + 1], acc[i][j][4 * qq + 2], acc[i][j][4 * qq + 3]);
-              acc[i][j][4 * qq + 0] -= __uint_as_float(w.x << 16);
-              acc[i][j][4 * qq + 1] -= __uint_as_float(w.x & 0xffff0000u);
-              acc[i][j][4 * qq + 2] -= __uint_as_float(w.y << 16);
-              acc[i][j][4 * qq + 3] -= __uint_as_float(w.y & 0xffff0000u);
-              if (qq == 3) __builtin_amdgcn_sched_barrier(0);
-            }
       }
     }
   }
