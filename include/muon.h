@@ -4,11 +4,11 @@
  * One call to muon_step() performs, for every 2-D matrix in a list, the update
  * rule of "Muon is Scalable for LLM Training" (arXiv 2502.16982):
  *
- *   M_t = mu * M_{t-1} + G                                  (section 2.1, update rule, line 1)
+ *   M_t = mu * M_{t-1} + G                                  (section 2.1, Eq. 1, the momentum recurrence)
  *   U   = M_t            or   mu * M_t + G  (Nesterov)      (section 2.1, footnote 1)
  *   X_0 = U / (||U||_F + eps), transposed so rows <= cols   (section 2.1, "Newton-Schulz Iterations")
  *   X_k = a X + b (X X^T) X + c (X X^T)^2 X,  k = 1..N      (Eq. 2)
- *   O   = X_N (transposed back)                             (Eq. 1)
+ *   O   = X_N (transposed back)                             (Eq. 1, O_t = Newton-Schulz(M_t))
  *   W_t = W_{t-1} - lr * (rms_scale * sqrt(max(A,B)) * O + weight_decay * W_{t-1})   (Eq. 4, contains Eq. 3)
  *
  * All buffer pointers are DEVICE pointers owned by the caller.  The library
