@@ -4,7 +4,7 @@
  * One call to muon_step() performs, for every 2-D matrix in a list, the update
  * rule of "Muon is Scalable for LLM Training" (arXiv 2502.16982):
  *
- *   M_t = mu * M_{t-1} + G                                  (section 2.1, Eq. 1, the momentum recurrence)
+ *   M_t = mu * M_{t-1} + G                                  (section 2.1, the recurrence printed above Eq. 1)
  *   U   = M_t            or   mu * M_t + G  (Nesterov)      (section 2.1, footnote 1)
  *   X_0 = U / (||U||_F + eps), transposed so rows <= cols   (section 2.1, "Newton-Schulz Iterations")
  *   X_k = a X + b (X X^T) X + c (X X^T)^2 X,  k = 1..N      (Eq. 2)
