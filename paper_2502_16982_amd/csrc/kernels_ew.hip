@@ -201,15 +201,20 @@ __device__ __forceinline__ void momentum_tile(const MatDesc& d, const MatPtrs& p
   const bool write_same = both || !d.transposed, write_flip = both || d.transposed;
   if (write_same) ns_store16<XT, PL>(same + (size_t)r * pitch_same + c0, (size_t)d.x_plane, u);
 
+  // the transposed tile goes through LDS; skipped (block-uniformly) where only the untransposed layout is wanted
   const int lr_ = tid >> 2, lc0 = (tid & 3) * 16;
+  if (write_flip) {
 #pragma unroll
-  for (int i = 0; i < 16; ++i) lds[lc0 + i][lr_] = u[i];
+    for (int i = 0; i < 16; ++i) lds[lc0 + i][lr_] = u[i];
+  }
   const float total = block_sum_256(ss, red);   // contains the barrier that publishes the LDS tile
-  float t[16];
-  const int fc = tid >> 2, fr0 = (tid & 3) * 16;   // row of U^T (= column of U), 16 consecutive columns of U^T
+  if (write_flip) {
+    float t[16];
+    const int fc = tid >> 2, fr0 = (tid & 3) * 16;   // row of U^T (= column of U), 16 consecutive columns of U^T
 #pragma unroll
-  for (int i = 0; i < 16; ++i) t[i] = lds[fc][fr0 + i];
-  if (write_flip) ns_store16<XT, PL>(flip + (size_t)(tc * kEwTile + fc) * pitch_flip + tr * kEwTile + fr0, (size_t)d.x_plane, t);
+    for (int i = 0; i < 16; ++i) t[i] = lds[fc][fr0 + i];
+    ns_store16<XT, PL>(flip + (size_t)(tc * kEwTile + fc) * pitch_flip + tr * kEwTile + fr0, (size_t)d.x_plane, t);
+  }
 
   if (tid == 0) d.partials[tr * d.ew_tiles_c + tc] = total;
 }
