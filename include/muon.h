@@ -143,6 +143,27 @@ int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t
 int muon_plan_chunks(const muon_ctx* ctx);
 
 /*
+ * Host only: builds the launch plan that muon_init would build for a workspace of `workspace_bytes`, without
+ * touching any device (no HIP call is made).  The context it returns can be given to muon_plan_describe,
+ * muon_plan_chunks, muon_plan_tiles and muon_destroy only; muon_step and muon_debug_read_update reject it.
+ * Same status codes as muon_init.
+ */
+int muon_plan_only(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dtype, size_t workspace_bytes);
+
+/*
+ * Host only: the tile table of one grouped launch of a context made by muon_plan_only.  `product`: 0 Gram
+ * (A = X X^T), 1 polynomial, 2 apply, 3 apply of the last iteration; `level`: 0 = the fine block tile
+ * (128 x 128 on the matrix-core paths, 64 x 64 on the fp32 path), 1 = 256 x 256 tiles (matrix-core paths only).
+ * Writes up to `cap_records` records of four int32 {matrix index in the list, tile row, tile column, block
+ * tile size}, in launch order, and returns the number of records of the table (which may exceed cap_records)
+ * or a negative status.  Tile rows and columns count in units of the block tile; Gram and polynomial tables
+ * hold the tiles on and above the diagonal of the m_pad x m_pad output; apply tables hold the tiles of
+ * X'^T (n_pad x m_pad) on the matrix-core paths and of X' (m_pad x n_pad) on the fp32 path.
+ */
+int muon_plan_tiles(const muon_ctx* ctx, int32_t chunk, int32_t product, int32_t level, int32_t* out,
+                    int32_t cap_records);
+
+/*
  * Per-kernel timing with HIP events on the step's own stream, for measurement (not part of the method).
  * While enabled, muon_step brackets every kernel launch with a pair of events; muon_profile_read waits for
  * the recorded work, adds the elapsed times per kernel class to running totals, copies the totals out

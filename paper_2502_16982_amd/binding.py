@@ -27,6 +27,7 @@ EXPORTS = (
     "muon_default_hparams", "muon_workspace_bytes", "muon_init", "muon_step", "muon_debug_read_update",
     "muon_plan_describe", "muon_plan_chunks", "muon_destroy", "muon_status_string", "muon_last_hip_error",
     "muon_profile_enable", "muon_profile_read", "muon_adamw_step", "muon_probe_mfma_rate",
+    "muon_plan_only", "muon_plan_tiles",
 )
 PROF_NAMES = ("momentum_norm_cast", "norm_finalize", "gram", "poly", "apply_poly", "weight_update", "update_rms")
 
@@ -114,6 +115,10 @@ def lib() -> C.CDLL:
     L.muon_profile_read.restype = C.c_int
     L.muon_probe_mfma_rate.argtypes = [C.c_int, C.c_int, P(C.c_double), P(C.c_double)]
     L.muon_probe_mfma_rate.restype = C.c_int
+    L.muon_plan_only.argtypes = [P(C.c_void_p), P(muon_param), C.c_int32, C.c_int32, C.c_size_t]
+    L.muon_plan_only.restype = C.c_int
+    L.muon_plan_tiles.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, P(C.c_int32), C.c_int32]
+    L.muon_plan_tiles.restype = C.c_int
     _LIB = L
     return L
 
@@ -212,6 +217,28 @@ def muon_plan_chunks(ctx) -> int:
     if k < 0:
         raise MuonError(k, "muon_plan_chunks")
     return k
+
+
+def muon_plan_only(params, n: int, ns_dtype: int, workspace_bytes: int) -> C.c_void_p:
+    """Host-only launch plan (no device is touched); release with muon_destroy."""
+    ctx = C.c_void_p(None)
+    _check(lib().muon_plan_only(C.byref(ctx), params, n, ns_dtype, workspace_bytes), "muon_plan_only")
+    return ctx
+
+
+PLAN_PRODUCTS = {"gram": 0, "poly": 1, "apply": 2, "apply_last": 3}
+
+
+def muon_plan_tiles(ctx, chunk: int, product: str, level: int) -> list:
+    """Tile table of one grouped launch of a host-only plan: [(matrix, tile_row, tile_col, tile_size), ...]."""
+    count = lib().muon_plan_tiles(ctx, chunk, PLAN_PRODUCTS[product], level, None, 0)
+    if count < 0:
+        raise MuonError(count, "muon_plan_tiles")
+    buf = (C.c_int32 * (4 * max(count, 1)))()
+    got = lib().muon_plan_tiles(ctx, chunk, PLAN_PRODUCTS[product], level, buf, count)
+    if got != count:
+        raise MuonError(got if got < 0 else -1, "muon_plan_tiles")
+    return [tuple(buf[4 * i:4 * i + 4]) for i in range(count)]
 
 
 def muon_profile_enable(ctx, enable: bool) -> None:

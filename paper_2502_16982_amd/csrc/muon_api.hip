@@ -58,6 +58,7 @@ struct TileSet {
 // the remaining strips, so that nothing is padded beyond the fine tile.
 struct Group {
   int n_prob;
+  std::vector<int> members;                       // problem index -> matrix index in the caller's list
   size_t prob_gram[2], prob_poly, prob_apply[4];  // byte offsets of the problem tables ([parity], [parity * 2 + last])
   TileSet fine, coarse;
 };
@@ -222,6 +223,9 @@ struct muon_ctx {
   std::vector<MatPtrs> last_ptrs;
   bool ptrs_valid = false;
   hipEvent_t upload_done = nullptr;
+  // host-only plan (muon_plan_only): no device tables exist; the table image is kept for muon_plan_tiles
+  bool plan_only = false;
+  std::vector<unsigned char> host_image;
   // state of the last step, for the debug read
   int last_o_sel = 0, last_use_s = 0, last_chunk = -1;
   // optional per-launch event timing
@@ -315,8 +319,14 @@ int muon_workspace_bytes(const muon_param* shapes, int32_t n, int32_t ns_dtype, 
   return MUON_OK;
 }
 
-int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dtype, void* workspace,
-              size_t workspace_bytes) {
+}  // extern "C"
+
+namespace {
+
+// Everything muon_init does short of touching the device: the plan and the host image of the table region.  With
+// `upload` the image goes to the workspace and the per-context HIP objects are created.
+int build_context(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dtype, void* workspace,
+                  size_t workspace_bytes, bool upload) {
   if (!out) return MUON_E_INVALID_ARG;
   *out = nullptr;
   int st = validate_shapes(shapes, n, ns_dtype);
@@ -433,6 +443,7 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
       });
       Group g{};
       g.n_prob = (int)members.size();
+      g.members = members;
       auto take = [&](size_t bytes) {
         cursor = align_up(cursor, 256);
         const size_t o = cursor;
@@ -537,6 +548,13 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
 
   ctx->d_mats = reinterpret_cast<MatDesc*>(dev(off_mats));
   ctx->d_ptrs = reinterpret_cast<MatPtrs*>(dev(off_ptrs));
+  if (!upload) {
+    ctx->plan_only = true;
+    img.resize(cursor);
+    ctx->host_image.swap(img);
+    *out = ctx;
+    return MUON_OK;
+  }
 
   hipError_t e = hipGetDevice(&ctx->device);
   if (e == hipSuccess) e = gemm_setup();
@@ -552,9 +570,44 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
   return MUON_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dtype, void* workspace,
+              size_t workspace_bytes) {
+  return build_context(out, shapes, n, ns_dtype, workspace, workspace_bytes, true);
+}
+
+int muon_plan_only(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dtype, size_t workspace_bytes) {
+  // table pointers are computed from the workspace address but never followed: any aligned non-null address will do
+  return build_context(out, shapes, n, ns_dtype, reinterpret_cast<void*>(uintptr_t{1} << 32), workspace_bytes, false);
+}
+
+int muon_plan_tiles(const muon_ctx* ctx, int32_t chunk, int32_t product, int32_t level, int32_t* out, int32_t cap_records) {
+  if (!ctx || !ctx->plan_only || chunk < 0 || chunk >= (int)ctx->chunks.size() || product < 0 || product > 3 || level < 0 ||
+      level > 1 || cap_records < 0 || (cap_records > 0 && !out))
+    return MUON_E_INVALID_ARG;
+  int64_t total = 0;
+  for (const Group& g : ctx->chunks[chunk].groups) {
+    const TileSet& ts = level ? g.coarse : g.fine;
+    const size_t off = product <= 1 ? ts.sym : product == 2 ? ts.apply : ts.apply_last;
+    const int count = product <= 1 ? ts.n_sym : product == 2 ? ts.n_apply : ts.n_apply_last;
+    const GemmTile* t = reinterpret_cast<const GemmTile*>(ctx->host_image.data() + off);
+    for (int i = 0; i < count; ++i, ++total) {
+      if (total >= cap_records) continue;
+      const int mat = g.members[t[i].prob];
+      const int size = level ? kCoarse : ctx->mats[mat].tile;
+      int32_t* r = out + 4 * total;
+      r[0] = mat; r[1] = t[i].ti; r[2] = t[i].tj; r[3] = size;
+    }
+  }
+  return (int)std::min<int64_t>(total, INT32_MAX);
+}
+
 int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hparams* hp, void* hip_stream,
               float* update_rms_out) {
-  if (!ctx || !params || !hp) return MUON_E_INVALID_ARG;
+  if (!ctx || !params || !hp || ctx->plan_only) return MUON_E_INVALID_ARG;
   if (n != ctx->n) return MUON_E_SHAPE_MISMATCH;
   if (hp->ns_steps < 0 || !(hp->eps >= 0.0) || !std::isfinite(hp->lr) || !std::isfinite(hp->weight_decay) ||
       !std::isfinite(hp->momentum) || !std::isfinite(hp->a) || !std::isfinite(hp->b) || !std::isfinite(hp->c) ||
@@ -661,7 +714,7 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
 }
 
 int muon_debug_read_update(muon_ctx* ctx, int32_t index, void* dst, int32_t dst_dtype, void* hip_stream) {
-  if (!ctx || !dst || index < 0 || index >= ctx->n) return MUON_E_INVALID_ARG;
+  if (!ctx || ctx->plan_only || !dst || index < 0 || index >= ctx->n) return MUON_E_INVALID_ARG;
   if (dst_dtype != MUON_F32 && dst_dtype != MUON_BF16) return MUON_E_UNSUPPORTED_DTYPE;
   if (ctx->last_chunk < 0 || ctx->mats[index].chunk != ctx->last_chunk) return MUON_E_NOT_RESIDENT;
   MUON_HIP(launch_read_update(ctx->d_mats, index, ctx->last_o_sel, ctx->last_use_s, ctx->ns_dtype, dst, dst_dtype,
@@ -680,7 +733,7 @@ int muon_plan_describe(const muon_ctx* ctx, int32_t index, int64_t* out, int32_t
 }
 
 int muon_profile_enable(muon_ctx* ctx, int enable) {
-  if (!ctx) return MUON_E_INVALID_ARG;
+  if (!ctx || ctx->plan_only) return MUON_E_INVALID_ARG;
   if (enable && ctx->prof_events.empty()) {
     ctx->prof_events.reserve(2 * kProfPairs);
     for (size_t i = 0; i < 2 * kProfPairs; ++i) {

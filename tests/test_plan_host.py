@@ -1,0 +1,124 @@
+"""Host logic of the launch planner, without a GPU: muon_plan_only builds the plan muon_init would build and
+muon_plan_tiles hands out its tile tables; the tests check that every product's tiles cover exactly the output they
+must, once, whatever the shape mix, the arithmetic and the chunking."""
+import numpy as np
+import pytest
+
+from paper_2502_16982_amd import binding
+
+SHAPE_SETS = {
+    "ragged": [(1, 1), (1, 9), (5, 3), (64, 64), (130, 130), (200, 333), (333, 200), (257, 511), (384, 128), (128, 640)],
+    "tiles256": [(1024, 1024), (1024, 1536), (1280, 1024), (384, 640), (640, 1152)],
+    "moe_expert": [(2048, 1408), (2048, 1408), (1408, 2048)],
+    "block": [(4096, 4096), (4096, 11008), (11008, 4096)],
+    "many_small": [(256, 384)] * 40 + [(384, 256)] * 30,
+    "extreme": [(4, 1 << 20), (1 << 20, 4), (1, 70000)],
+}
+
+
+def plan(shapes, ns, max_bytes=0):
+    n = len(shapes)
+    p = binding.param_array(shapes, [1] * n, [1] * n)
+    need = binding.muon_workspace_bytes(p, n, ns, max_bytes)
+    return binding.muon_plan_only(p, n, ns, need), p
+
+
+@pytest.mark.parametrize("ns", [binding.MUON_BF16, binding.MUON_BF16X2, binding.MUON_F32])
+@pytest.mark.parametrize("name", sorted(SHAPE_SETS))
+def test_every_output_tile_is_computed_exactly_once(name, ns):
+    shapes = SHAPE_SETS[name]
+    ctx, _ = plan(shapes, ns)
+    try:
+        assert binding.muon_plan_chunks(ctx) == 1
+        desc = [binding.muon_plan_describe(ctx, i) for i in range(len(shapes))]
+        mc = ns != binding.MUON_F32
+        for product in ("gram", "poly", "apply", "apply_last"):
+            sym = product in ("gram", "poly")
+            cover = {}
+            for i, d in enumerate(desc):
+                fine = d["tile_n"]
+                tm, tn = d["m_pad"] // fine, d["n_pad"] // fine
+                # output grid in fine tiles: m x m for the symmetric products; X'^T (n x m) on the matrix cores, X' else
+                cover[i] = np.zeros((tm, tm) if sym else ((tn, tm) if mc else (tm, tn)), dtype=np.int32)
+            for level in (0, 1):
+                for mat, ti, tj, size in binding.muon_plan_tiles(ctx, 0, product, level):
+                    fine = desc[mat]["tile_n"]
+                    assert size == (256 if level else fine) and size % fine == 0
+                    r = size // fine
+                    grid = cover[mat]
+                    assert 0 <= ti * r and (ti + 1) * r <= grid.shape[0] and 0 <= tj * r and (tj + 1) * r <= grid.shape[1]
+                    if sym:
+                        assert tj >= ti
+                    grid[ti * r:(ti + 1) * r, tj * r:(tj + 1) * r] += 1
+            for i, grid in cover.items():
+                if sym:
+                    # tiles on or above the diagonal once (a diagonal block tile also covers its own lower part)
+                    upper = np.triu(np.ones_like(grid))
+                    assert (grid[upper == 1] == 1).all(), (name, product, shapes[i])
+                    low = np.tril(grid, -1)
+                    r = 256 // desc[i]["tile_n"] if mc else 1
+                    blocks_i, blocks_j = np.nonzero(low)
+                    assert all(bi // r == bj // r for bi, bj in zip(blocks_i, blocks_j)), (name, product, shapes[i])
+                else:
+                    assert (grid == 1).all(), (name, product, shapes[i])
+    finally:
+        binding.lib().muon_destroy(ctx)
+
+
+def test_orientation_padding_and_tile_sizes():
+    shapes = [(2048, 1408), (1408, 2048), (100, 130), (4096, 4096)]
+    ctx, _ = plan(shapes, binding.MUON_BF16)
+    try:
+        d = [binding.muon_plan_describe(ctx, i) for i in range(4)]
+        assert [x["transposed"] for x in d] == [1, 0, 0, 0]
+        assert [(x["m"], x["n"]) for x in d] == [(1408, 2048), (1408, 2048), (100, 130), (4096, 4096)]
+        assert [(x["m_pad"], x["n_pad"]) for x in d] == [(1408, 2048), (1408, 2048), (128, 256), (4096, 4096)]
+        assert [x["tile_m"] for x in d] == [256, 256, 128, 256] and all(x["tile_n"] == 128 for x in d)
+        # 1408 = 5 x 256 + 128: fifteen 256-tiles on or above the diagonal, eleven 128-tiles in the strip
+        gram256 = [t for t in binding.muon_plan_tiles(ctx, 0, "gram", 1) if t[0] == 0]
+        gram128 = [t for t in binding.muon_plan_tiles(ctx, 0, "gram", 0) if t[0] == 0]
+        assert len(gram256) == 15 and len(gram128) == 11
+        apply256 = [t for t in binding.muon_plan_tiles(ctx, 0, "apply", 1) if t[0] == 0]
+        apply128 = [t for t in binding.muon_plan_tiles(ctx, 0, "apply", 0) if t[0] == 0]
+        assert len(apply256) == 8 * 5 and len(apply128) == 16
+    finally:
+        binding.lib().muon_destroy(ctx)
+
+
+def test_chunked_plan_keeps_each_matrix_in_one_chunk():
+    shapes = [(256, 384)] * 5 + [(384, 256)] * 3
+    n = len(shapes)
+    p = binding.param_array(shapes, [1] * n, [1] * n)
+    small = binding.muon_workspace_bytes(p, n, binding.MUON_BF16, 1)       # room for one matrix at a time
+    ctx = binding.muon_plan_only(p, n, binding.MUON_BF16, small)
+    try:
+        chunks = binding.muon_plan_chunks(ctx)
+        assert chunks == n
+        seen = set()
+        for c in range(chunks):
+            mats = {t[0] for level in (0, 1) for t in binding.muon_plan_tiles(ctx, c, "apply", level)}
+            assert len(mats) == 1 and not (mats & seen)
+            assert {binding.muon_plan_describe(ctx, m)["chunk"] for m in mats} == {c}
+            seen |= mats
+        assert seen == set(range(n))
+    finally:
+        binding.lib().muon_destroy(ctx)
+
+
+def test_plan_only_contexts_are_rejected_by_device_entry_points():
+    import ctypes as C
+    ctx, p = plan([(128, 256)], binding.MUON_BF16)
+    L = binding.lib()
+    try:
+        hp = binding.default_hparams()
+        assert L.muon_step(ctx, p, 1, C.byref(hp), None, None) == -1
+        assert L.muon_debug_read_update(ctx, 0, C.c_void_p(256), 0, None) == -1
+        assert L.muon_profile_enable(ctx, 1) == -1
+        assert L.muon_plan_tiles(ctx, 1, 0, 0, None, 0) == -1      # no such chunk
+        assert L.muon_plan_tiles(ctx, 0, 4, 0, None, 0) == -1
+        assert L.muon_plan_tiles(ctx, 0, 0, 2, None, 0) == -1
+    finally:
+        L.muon_destroy(ctx)
+    ctx = C.c_void_p(None)
+    assert L.muon_plan_only(C.byref(ctx), p, 1, binding.MUON_BF16, 16) == -4
+    assert ctx.value is None
