@@ -122,3 +122,23 @@ def test_plan_only_contexts_are_rejected_by_device_entry_points():
     ctx = C.c_void_p(None)
     assert L.muon_plan_only(C.byref(ctx), p, 1, binding.MUON_BF16, 16) == -4
     assert ctx.value is None
+
+
+@pytest.mark.parametrize("name", ["dense12_w1024", "block_w4096", "moe_bank_66x2048x1408"])
+def test_bench_counts_the_flops_the_plan_issues(name):
+    """bench.py's executed-flop figure is recomputed from shapes; it must equal what the planner's tile tables issue."""
+    import bench
+    from paper_2502_16982_amd import workloads
+    wl = workloads.workload(name)
+    shapes = list(wl.shapes)
+    ctx, _ = plan(shapes, binding.MUON_BF16)
+    try:
+        desc = [binding.muon_plan_describe(ctx, i) for i in range(len(shapes))]
+        flops = 0
+        for product, k_of in (("gram", "n_pad"), ("poly", "m_pad"), ("apply", "m_pad")):
+            for level in (0, 1):
+                for mat, _, _, size in binding.muon_plan_tiles(ctx, 0, product, level):
+                    flops += 2 * size * size * desc[mat][k_of]
+        assert bench.executed_ns_flops(wl, 1, 128, 256) == flops
+    finally:
+        binding.lib().muon_destroy(ctx)
