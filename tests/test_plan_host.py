@@ -142,3 +142,27 @@ def test_bench_counts_the_flops_the_plan_issues(name):
         assert bench.executed_ns_flops(wl, 1, 128, 256) == flops
     finally:
         binding.lib().muon_destroy(ctx)
+
+
+@pytest.mark.parametrize("shape,product", [((4096, 4096), "gram"), ((4096, 11008), "apply"), ((11008, 4096), "apply")])
+def test_tiles_that_run_together_on_a_die_share_operand_panels(shape, product):
+    """Entry b of a tile table runs on accelerator die b % 8 (workgroups are handed out round-robin), one tile per
+    compute unit, 32 at a time.  A die's sequence is a contiguous run of a blocked order of the tile grid (4 x 8 or
+    8 x 4 blocks), so any 32 consecutive tiles of it lie in at most two blocks and touch at most 2 x 12 operand panels
+    in that die's L2, against 33 for a row-major run; the first die's first 32 tiles are one whole block."""
+    ctx, _ = plan([shape], binding.MUON_BF16)
+    try:
+        tiles = binding.muon_plan_tiles(ctx, 0, product, 1)
+        worst = 0
+        for die in range(8):
+            seq = tiles[die::8]
+            width = min(32, len(seq))
+            for start in range(0, len(seq) - width + 1, width):
+                block = seq[start:start + width]
+                worst = max(worst, len({t[1] for t in block}) + len({t[2] for t in block}))
+        assert worst <= 24, worst
+        if product == "apply":
+            first = tiles[0::8][:32]
+            assert len({t[1] for t in first}) + len({t[2] for t in first}) == 12
+    finally:
+        binding.lib().muon_destroy(ctx)
