@@ -31,7 +31,7 @@ DEFAULT_CONFIG = "block_w4096"
 OTHER_WORKLOADS = ("block_w4096", "dense12_w1024", "moe_bank_66x2048x1408")
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (counter KiB x 1024 x copy-calibration factor 2.0 for fetch, 1.0 for write).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1286043 * 2.0 + 290693 * 1.0) * 1024),
+MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1247140 * 2.0 + 290693 * 1.0) * 1024),
                           "dense12_w1024": int((234849 * 2.0 + 251536 * 1.0) * 1024),
                           # 256x256-tile launches only (the 128x128 strip launches move another 1.23 GB each)
                           "moe_bank_66x2048x1408": int((985112 * 2.0 + 776820 * 1.0) * 1024)}

@@ -97,20 +97,26 @@ constexpr int kXcds = 8;
 // 4 x 8 blocks of the tile grid: the 32 tiles running together on an XCD then share 4 row panels and 8 column
 // panels, which they sweep along k in step, instead of 1 + 32 panels for a row-major run.
 // Tiles (i, j) with i < skip_m and j < skip_n are left out (they are covered by the coarser kernel).
+// `cuts` receives the list positions at which a block ends.
 void blocked_tiles(int32_t prob, int tm, int tn, bool upper_only, int skip_m, int skip_n, std::vector<GemmTile>& out,
-                   int BH = 4, int BW = 8) {
+                   std::vector<int>& cuts, int BH = 4, int BW = 8) {
   for (int bi = 0; bi < tm; bi += BH)
-    for (int bj = 0; bj < tn; bj += BW)
+    for (int bj = 0; bj < tn; bj += BW) {
       for (int i = bi; i < std::min(bi + BH, tm); ++i)
         for (int j = bj; j < std::min(bj + BW, tn); ++j)
           if ((!upper_only || j >= i) && !(i < skip_m && j < skip_n)) out.push_back(GemmTile{prob, (int16_t)i, (int16_t)j});
+      if (!out.empty() && (cuts.empty() || cuts.back() != (int)out.size())) cuts.push_back((int)out.size());
+    }
 }
 
-size_t deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTile* out) {
+size_t deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, const std::vector<std::vector<int>>& per_problem_cuts,
+                  GemmTile* out) {
   std::vector<std::vector<GemmTile>> seq(kXcds);
   int rr = 0;
   const bool whole = per_problem.size() >= 4 * (size_t)kXcds;
-  for (const std::vector<GemmTile>& tiles : per_problem) {
+  for (size_t pi = 0; pi < per_problem.size(); ++pi) {
+    const std::vector<GemmTile>& tiles = per_problem[pi];
+    const std::vector<int>& cuts = per_problem_cuts[pi];
     if (whole) {
       // least-loaded XCD, ties broken round-robin
       int best = rr;
@@ -119,10 +125,23 @@ size_t deal_tiles(const std::vector<std::vector<GemmTile>>& per_problem, GemmTil
       seq[best].insert(seq[best].end(), tiles.begin(), tiles.end());
       rr = (rr + 1) % kXcds;
     } else {
+      // 8 contiguous runs of equal length (so that entry b of the dealt table still lands on die b % 8).  A run
+      // starts and ends inside blocks; its whole blocks go first, so that the tiles a die runs together come from
+      // one block, and the two partial blocks at its ends follow.
       const size_t n = tiles.size();
       for (int x = 0; x < kXcds; ++x) {
         const size_t lo = n * x / kXcds, hi = n * (x + 1) / kXcds;
-        seq[x].insert(seq[x].end(), tiles.begin() + lo, tiles.begin() + hi);
+        size_t c0 = lo, c1 = lo;                   // first and last block boundary inside [lo, hi] (none: c0 = c1 = lo)
+        bool found = false;
+        for (int c : cuts)
+          if ((size_t)c >= lo && (size_t)c <= hi) {
+            if (!found) c0 = (size_t)c;
+            c1 = (size_t)c;
+            found = true;
+          }
+        seq[x].insert(seq[x].end(), tiles.begin() + c0, tiles.begin() + c1);
+        seq[x].insert(seq[x].end(), tiles.begin() + lo, tiles.begin() + c0);
+        seq[x].insert(seq[x].end(), tiles.begin() + c1, tiles.begin() + hi);
       }
     }
   }
@@ -509,21 +528,22 @@ int build_context(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t n
       for (int level = 1; level >= 0; --level) {
         if (level == 1 && !on_matrix_cores(ns_dtype)) continue;
         std::vector<std::vector<GemmTile>> sym(members.size()), app(members.size()), app_last(members.size());
+        std::vector<std::vector<int>> sym_cuts(members.size()), app_cuts(members.size());
         size_t n_sym = 0, n_app = 0, n_last = 0;
         for (size_t k = 0; k < members.size(); ++k) {
           const MatPlan& q = ctx->mats[members[k]];
           const int cm = on_matrix_cores(ns_dtype) ? q.mp / kCoarse : 0, cn = on_matrix_cores(ns_dtype) ? q.np / kCoarse : 0;
           if (level == 1) {
-            blocked_tiles((int32_t)k, cm, cm, true, 0, 0, sym[k]);
+            blocked_tiles((int32_t)k, cm, cm, true, 0, 0, sym[k], sym_cuts[k]);
             // tiles of X'^T; 8 x 4 blocks measured 1 % faster than 4 x 8 here (the K-major panels are the strided ones)
-            if (on_matrix_cores(ns_dtype)) blocked_tiles((int32_t)k, cn, cm, false, 0, 0, app[k], 8, 4);
-            else blocked_tiles((int32_t)k, cm, cn, false, 0, 0, app[k]);
+            if (on_matrix_cores(ns_dtype)) blocked_tiles((int32_t)k, cn, cm, false, 0, 0, app[k], app_cuts[k], 8, 4);
+            else blocked_tiles((int32_t)k, cm, cn, false, 0, 0, app[k], app_cuts[k]);
             app_last[k] = app[k];
           } else {
             const int tm = q.mp / q.tile, tn = q.np / q.tile, r = kCoarse / q.tile;
-            blocked_tiles((int32_t)k, tm, tm, true, cm * r, cm * r, sym[k]);
-            if (on_matrix_cores(ns_dtype)) blocked_tiles((int32_t)k, tn, tm, false, cn * r, cm * r, app[k], 8, 4);
-            else blocked_tiles((int32_t)k, tm, tn, false, cm * r, cn * r, app[k]);
+            blocked_tiles((int32_t)k, tm, tm, true, cm * r, cm * r, sym[k], sym_cuts[k]);
+            if (on_matrix_cores(ns_dtype)) blocked_tiles((int32_t)k, tn, tm, false, cn * r, cm * r, app[k], app_cuts[k], 8, 4);
+            else blocked_tiles((int32_t)k, tm, tn, false, cm * r, cn * r, app[k], app_cuts[k]);
             app_last[k] = app[k];
           }
           n_sym += sym[k].size();
@@ -534,9 +554,9 @@ int build_context(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t n
         ts.sym = take(n_sym * sizeof(GemmTile));
         ts.apply = take(n_app * sizeof(GemmTile));
         ts.apply_last = take(n_last * sizeof(GemmTile));
-        ts.n_sym = (int)deal_tiles(sym, reinterpret_cast<GemmTile*>(img.data() + ts.sym));
-        ts.n_apply = (int)deal_tiles(app, reinterpret_cast<GemmTile*>(img.data() + ts.apply));
-        ts.n_apply_last = (int)deal_tiles(app_last, reinterpret_cast<GemmTile*>(img.data() + ts.apply_last));
+        ts.n_sym = (int)deal_tiles(sym, sym_cuts, reinterpret_cast<GemmTile*>(img.data() + ts.sym));
+        ts.n_apply = (int)deal_tiles(app, app_cuts, reinterpret_cast<GemmTile*>(img.data() + ts.apply));
+        ts.n_apply_last = (int)deal_tiles(app_last, app_cuts, reinterpret_cast<GemmTile*>(img.data() + ts.apply_last));
       }
       ch.groups.push_back(g);
     }
