@@ -28,35 +28,59 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x
 PEAK_F32_VALU_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 DEFAULT_CONFIG = "block_w4096"
-OTHER_WORKLOADS = ("block_w4096", "dense12_w1024", "moe_bank_66x2048x1408")
-# HBM bytes per launch of the dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised under
-# profiles/ (counter KiB x 1024 x copy-calibration factor 2.0 for fetch, 1.0 for write).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {"block_w4096": int((1247140 * 2.0 + 290693 * 1.0) * 1024),
-                          "dense12_w1024": int((234849 * 2.0 + 251536 * 1.0) * 1024),
-                          # 256x256-tile launches only (the 128x128 strip launches move another 1.23 GB each)
-                          "moe_bank_66x2048x1408": int((985112 * 2.0 + 776820 * 1.0) * 1024)}
+# every single-GPU workload of the target: (name, timed steps, warm-up steps) when it is not the headline
+OTHER_WORKLOADS = (("block_w4096", 5, 2), ("dense12_w1024", 5, 2), ("moe_bank_66x2048x1408", 5, 2), ("moe27_w2048", 3, 1))
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
 
-def executed_ns_flops(wl, ns_steps, fine, coarse):
-    """MFMA flops actually issued: symmetric products compute only tiles on or above the diagonal; the part of
-    an output that whole `coarse` tiles cover uses them, the remaining strips use `fine` tiles."""
-    def tiles(tm, tn, upper, skip_m=0, skip_n=0):
-        return sum(1 for i in range(tm) for j in range(tn) if (not upper or j >= i) and not (i < skip_m and j < skip_n))
-    tot = 0
-    cache = {}
-    for (a, b) in wl.shapes:
-        m, n = min(a, b), max(a, b)
-        if (m, n) not in cache:
-            mp, np_ = -(-m // fine) * fine, -(-n // fine) * fine
-            cm, cn = (mp // coarse, np_ // coarse) if coarse else (0, 0)
-            r = coarse // fine if coarse else 1
-            sym_c, app_c = tiles(cm, cm, True), tiles(cm, cn, False)
-            sym_f = tiles(mp // fine, mp // fine, True, cm * r, cm * r)
-            app_f = tiles(mp // fine, np_ // fine, False, cm * r, cn * r)
-            area = lambda c, f: c * coarse * coarse + f * fine * fine
-            cache[(m, n)] = 2 * (area(sym_c, sym_f) * np_ + area(sym_c, sym_f) * mp + area(app_c, app_f) * mp)
-        tot += ns_steps * cache[(m, n)]
-    return tot
+def measured_traffic(workload, ns_dtype):
+    """HBM-side bytes per launch of the dominant kernel, from profiles/traffic.json: rocprofv3 FETCH_SIZE /
+    WRITE_SIZE runs of this same script (commands and commit recorded there), scaled by the counters' reading for a
+    plain copy (--calibrate-copy).  Not measured by this run; None when no profile covers the workload."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            entry = json.load(f)["workloads"].get(f"{workload}:{ns_dtype}")
+    except (OSError, ValueError, KeyError):
+        return None, None
+    if not entry:
+        return None, None
+    return int(entry["bytes_per_launch"]), f"profiles/traffic.json ({entry.get('measured_at', 'unknown commit')}), not this run"
+
+
+def calibrate_copy(mib=1024, repeats=5):
+    """Plain device-to-device copies of a known size, for calibrating rocprofv3's FETCH_SIZE / WRITE_SIZE counters:
+    each repeat is one torch copy kernel that reads and writes exactly `mib` MiB."""
+    import torch
+    n = mib * 2 ** 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(repeats):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_bytes": n, "repeats": repeats}), flush=True)
+    return 0
+
+
+def executed_ns_flops(wl, ns_steps, ns_dtype="bf16"):
+    """Matrix-core flops actually issued, summed over the tile tables of the launch plan (host-only call into the
+    library): symmetric products compute only tiles on or above the diagonal; strip tiles that were shifted to end at
+    the matrix edge recompute what they overlap."""
+    from paper_2502_16982_amd import binding
+    n = len(wl.shapes)
+    p = binding.param_array(wl.shapes, [1] * n, [1] * n)
+    ns = binding.NS_DTYPES[ns_dtype]
+    ctx = binding.muon_plan_only(p, n, ns, binding.muon_workspace_bytes(p, n, ns, 0))
+    try:
+        desc = [binding.muon_plan_describe(ctx, i) for i in range(n)]
+        flops = 0
+        for product, k_of in (("gram", "n_pad"), ("poly", "m_pad"), ("apply", "m_pad")):
+            for level in (0, 1):
+                for mat, _, _, rows, cols in binding.muon_plan_tiles(ctx, 0, product, level):
+                    flops += 2 * rows * cols * desc[mat][k_of]
+    finally:
+        binding.muon_destroy(ctx)
+    return ns_steps * flops
 
 
 def cpu_baseline(wl, budget_s=25.0):
@@ -167,7 +191,7 @@ def time_workload(name, steps, warmup, max_ws_gib, dev, ns_dtype=None):
     gemm_launches = sum(prof[k][1] for k in ("gram", "poly", "apply_poly"))
     bf16 = wl.ns_dtype != "f32"              # the matrix-core paths: plain bf16 and the split forms
     planes = PLANES[wl.ns_dtype]
-    executed = executed_ns_flops(wl, h.ns_steps, 128 if bf16 else 64, 256 if bf16 else 0) * SEGMENTS[planes]
+    executed = executed_ns_flops(wl, h.ns_steps, wl.ns_dtype) * SEGMENTS[planes]
     peak = PEAK_BF16_TFLOPS if bf16 else PEAK_F32_VALU_TFLOPS
     if gemm_launches:
         avg_launch_ms = gemm_ms / gemm_launches
@@ -175,8 +199,9 @@ def time_workload(name, steps, warmup, max_ws_gib, dev, ns_dtype=None):
         achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
     else:
         avg_launch_ms, flops_per_launch, achieved = 0.0, 0.0, 0.0
+    traffic, traffic_source = measured_traffic(wl.name, wl.ns_dtype)
     roofline = {"bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if wl.ns_dtype == "bf16" else None,
+                "frac": achieved / peak, "traffic": traffic, "traffic_source": traffic_source,
                 "kernel": "ns_gemm_bf16_kernel" if bf16 else "ns_gemm_f32_kernel",
                 "avg_launch_ms": avg_launch_ms, "launches_per_step": gemm_launches / max(steps, 1),
                 "nominal_flops_per_launch": flops_per_launch,
@@ -215,6 +240,8 @@ def main() -> int:
     ap.add_argument("--max-workspace-gib", type=float, default=16.0)
     ap.add_argument("--ns-dtype", choices=sorted(PLANES), default=None,
                     help="Newton-Schulz arithmetic of --config (default: the workload's own, bf16 for the headline)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run five plain 1 GiB device copies (counter calibration under rocprofv3 --pmc) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -228,6 +255,8 @@ def main() -> int:
         return 2
     binding.lib()
     dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        return calibrate_copy()
     r = time_workload(args.config, args.steps, args.warmup, args.max_workspace_gib, dev, args.ns_dtype)
     wl, h, bf16 = r["wl"], r["hyper"], r["bf16"]
     elapsed, ms_per_step, nominal, executed = r["elapsed"], r["ms_per_step"], r["nominal"], r["executed"]
@@ -255,20 +284,25 @@ def main() -> int:
         # The other single-GPU workloads of the target, each through the same timed loop (fewer steps); the headline
         # fields above stay those of --config.
         out["other_workloads"] = []
-        for other in OTHER_WORKLOADS:
+        for other, o_steps, o_warm in OTHER_WORKLOADS:
             if other == args.config:
                 continue
-            o = time_workload(other, max(2, args.steps // 2), 2, args.max_workspace_gib, dev)
+            o = time_workload(other, o_steps, o_warm, args.max_workspace_gib, dev)
             out["other_workloads"].append({
-                "workload": other, "ms_per_step": o["ms_per_step"], "steps_per_s": 1e3 / o["ms_per_step"],
+                "workload": other, "steps": o_steps, "warmup": o_warm, "matrices": len(o["wl"].shapes), "elements": o["n_el"],
+                "chunks": o["chunks"], "workspace_bytes": o["workspace_bytes"],
+                "ms_per_step": o["ms_per_step"], "steps_per_s": 1e3 / o["ms_per_step"],
                 "ms_per_step_median": o["ms_per_step_median"], "ms_per_step_min": o["ms_per_step_min"],
+                "ns_tflops_whole_step": o["nominal"] / (o["ms_per_step"] * 1e-3) / 1e12,
                 "ns_gemm_tflops_nominal": o["roofline"]["achieved"], "frac_of_bf16_peak": o["roofline"]["frac"],
                 "ns_gemm_tflops_executed": o["roofline"]["executed_tflops"],
                 "avg_gemm_launch_ms": o["roofline"]["avg_launch_ms"], "launches_per_step": o["roofline"]["launches_per_step"],
+                "roofline": o["roofline"],
+                "kernel_ms_per_step": {k: v[0] / o_steps for k, v in o["prof"].items() if v[1]},
                 "elementwise": o["elementwise"]})
         if args.ns_dtype is None:
             # the accurate matrix-core path on the headline workload: two bf16 planes, three products per product of Eq. 2
-            o = time_workload(args.config, max(2, args.steps // 2), 2, args.max_workspace_gib, dev, "bf16x2")
+            o = time_workload(args.config, min(5, max(2, args.steps // 2)), 2, args.max_workspace_gib, dev, "bf16x2")
             out["accurate_path"] = {
                 "workload": args.config, "ns_dtype": "bf16x2", "ms_per_step": o["ms_per_step"],
                 "ms_per_step_median": o["ms_per_step_median"], "steps_per_s": 1e3 / o["ms_per_step"],

@@ -14,7 +14,8 @@
  * All buffer pointers are DEVICE pointers owned by the caller.  The library
  * never allocates device memory: it works inside a caller-provided workspace.
  * Every function returns MUON_OK (0) or a negative muon_status; nothing here
- * throws, aborts or prints.  A context is not thread-safe; distinct contexts are
+ * throws (C++ exceptions inside the library, such as a failed host allocation, are caught at the boundary and
+ * reported as a status), aborts or prints.  A context is not thread-safe; distinct contexts are
  * independent.  All work of muon_step() is enqueued on the caller's HIP stream
  * and the call returns without synchronising with the device.
  */
@@ -47,7 +48,8 @@ typedef enum {
   MUON_E_WORKSPACE_TOO_SMALL = -4, /* workspace cannot hold the tables plus the largest single matrix  */
   MUON_E_HIP = -5,                 /* a HIP runtime call failed (see muon_last_hip_error)              */
   MUON_E_NOT_RESIDENT = -6,        /* debug read of a matrix whose workspace has been reused           */
-  MUON_E_MISALIGNED = -7           /* a buffer pointer is not aligned to its element size              */
+  MUON_E_MISALIGNED = -7,          /* a buffer pointer is not aligned to its element size              */
+  MUON_E_NO_MEMORY = -8            /* host memory for the plan or its tables could not be allocated    */
 } muon_status;
 
 /* The three ways of controlling the update RMS compared in section 3.1; the update is
@@ -152,13 +154,15 @@ int muon_plan_only(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t 
 
 /*
  * Host only: the tile table of one grouped launch of a context made by muon_plan_only.  `product`: 0 Gram
- * (A = X X^T), 1 polynomial, 2 apply, 3 apply of the last iteration; `level`: 0 = the fine block tile
- * (128 x 128 on the matrix-core paths, 64 x 64 on the fp32 path), 1 = 256 x 256 tiles (matrix-core paths only).
- * Writes up to `cap_records` records of four int32 {matrix index in the list, tile row, tile column, block
- * tile size}, in launch order, and returns the number of records of the table (which may exceed cap_records)
- * or a negative status.  Tile rows and columns count in units of the block tile; Gram and polynomial tables
- * hold the tiles on and above the diagonal of the m_pad x m_pad output; apply tables hold the tiles of
- * X'^T (n_pad x m_pad) on the matrix-core paths and of X' (m_pad x n_pad) on the fp32 path.
+ * (A = X X^T), 1 polynomial, 2 apply, 3 apply of the last iteration; `level`: 1 = the coarse launch of the
+ * matrix-core paths (256 x 256 tiles, plus 512 x 128 tiles over the 128-wide column strip that an m_pad which is an
+ * odd multiple of 128 leaves), 0 = the fine launch that takes the rest (128 x 128 tiles on the matrix-core paths,
+ * 64 x 64 on the fp32 path, which has no coarse launch).  Writes up to `cap_records` records of five int32
+ * {matrix index in the list, first row, first column, rows, columns} (in elements), in launch order, and returns the
+ * number of records of the table (which may exceed cap_records) or a negative status.  Gram and polynomial tables
+ * hold tiles on and above the diagonal of the m_pad x m_pad output; apply tables hold the tiles of X'^T
+ * (n_pad x m_pad) on the matrix-core paths and of X' (m_pad x n_pad) on the fp32 path.  The last 512 x 128 tile of
+ * a strip is shifted to end at the matrix edge and may overlap its neighbour (both then write the same values).
  */
 int muon_plan_tiles(const muon_ctx* ctx, int32_t chunk, int32_t product, int32_t level, int32_t* out,
                     int32_t cap_records);

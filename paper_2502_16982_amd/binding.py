@@ -20,7 +20,7 @@ MUON_SCALE_ADJUSTED_LR, MUON_SCALE_BASELINE, MUON_SCALE_UPDATE_NORM = 0, 1, 2
 MUON_OK = 0
 STATUS_NAMES = {
     0: "MUON_OK", -1: "MUON_E_INVALID_ARG", -2: "MUON_E_UNSUPPORTED_DTYPE", -3: "MUON_E_SHAPE_MISMATCH",
-    -4: "MUON_E_WORKSPACE_TOO_SMALL", -5: "MUON_E_HIP", -6: "MUON_E_NOT_RESIDENT", -7: "MUON_E_MISALIGNED",
+    -4: "MUON_E_WORKSPACE_TOO_SMALL", -5: "MUON_E_HIP", -6: "MUON_E_NOT_RESIDENT", -7: "MUON_E_MISALIGNED", -8: "MUON_E_NO_MEMORY",
 }
 
 EXPORTS = (
@@ -230,15 +230,15 @@ PLAN_PRODUCTS = {"gram": 0, "poly": 1, "apply": 2, "apply_last": 3}
 
 
 def muon_plan_tiles(ctx, chunk: int, product: str, level: int) -> list:
-    """Tile table of one grouped launch of a host-only plan: [(matrix, tile_row, tile_col, tile_size), ...]."""
+    """Tile table of one grouped launch of a host-only plan: [(matrix, row0, col0, rows, cols), ...] in elements."""
     count = lib().muon_plan_tiles(ctx, chunk, PLAN_PRODUCTS[product], level, None, 0)
     if count < 0:
         raise MuonError(count, "muon_plan_tiles")
-    buf = (C.c_int32 * (4 * max(count, 1)))()
+    buf = (C.c_int32 * (5 * max(count, 1)))()
     got = lib().muon_plan_tiles(ctx, chunk, PLAN_PRODUCTS[product], level, buf, count)
     if got != count:
         raise MuonError(got if got < 0 else -1, "muon_plan_tiles")
-    return [tuple(buf[4 * i:4 * i + 4]) for i in range(count)]
+    return [tuple(buf[5 * i:5 * i + 5]) for i in range(count)]
 
 
 def muon_profile_enable(ctx, enable: bool) -> None:

@@ -83,21 +83,33 @@ struct TileCfg {
 // s_waitcnt lgkmcnt(0), vmcnt untouched: this wave's LDS reads have returned
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8)); }
 
-// Optional timing probes, compiled in only with -DMUON_DBG_TIMING (never in the library build): per block
-// {start, main loop done, block done} wall-clock stamps (100 MHz) plus the hardware id of the compute unit, and
-// core-clock stamps of the pipeline phases and epilogue stages of one block.  A host harness reads the symbols.
-#ifdef MUON_DBG_TIMING
-__device__ long long g_dbg_t[64 * 8];
-__device__ long long g_dbg_blk[8192 * 4];
-__device__ long long g_dbg_clk[8192 * 2];
-#define DBG_E(slot) do { if (blockIdx.x == 300 && tid == 0) g_dbg_t[400 + (slot)] = clock64(); } while (0)
-#define DBG_BLK(slot) do { if (tid == 0 && blockIdx.x < 8192) g_dbg_blk[blockIdx.x * 4 + (slot)] = (slot) == 3 ? (long long)__builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)) | ((long long)__builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (31 << 11)) << 32) : (long long)wall_clock64(); } while (0)
-#define DBG_T(slot) do { if (blockIdx.x == 300 && tid == 0 && kt >= 8 && kt < 16) g_dbg_t[(kt - 8) * 8 + (slot)] = clock64(); } while (0)
-#else
-#define DBG_T(slot) do {} while (0)
-#define DBG_BLK(slot) do {} while (0)
-#define DBG_E(slot) do {} while (0)
-#endif
+// Hand-placed LDS waits whose covered registers are read-write operands of the wait itself (see the K-major path of
+// the kernel): s_waitcnt lgkmcnt(CNT) "producing" the A-side fragment halves of one k-step, and empty statements that
+// tie further registers to the same point.  An asm statement takes at most 30 operands, hence the split.
+template <int CNT>
+__device__ __forceinline__ void wait_lgkm_tie(u32x2 (&h)[4][2]) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(h[0][0]), "+v"(h[0][1]), "+v"(h[1][0]), "+v"(h[1][1]), "+v"(h[2][0]), "+v"(h[2][1]), "+v"(h[3][0]), "+v"(h[3][1])
+               : "n"(CNT)
+               : "memory");
+}
+template <int CNT>
+__device__ __forceinline__ void wait_lgkm_tie(u32x2 (&h)[2][2]) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(h[0][0]), "+v"(h[0][1]), "+v"(h[1][0]), "+v"(h[1][1]) : "n"(CNT) : "memory");
+}
+__device__ __forceinline__ void tie_regs(u32x2 (&h)[4][2]) {
+  asm volatile(""
+               : "+v"(h[0][0]), "+v"(h[0][1]), "+v"(h[1][0]), "+v"(h[1][1]), "+v"(h[2][0]), "+v"(h[2][1]), "+v"(h[3][0]), "+v"(h[3][1])
+               :
+               : "memory");
+}
+__device__ __forceinline__ void tie_regs(u32x2 (&h)[2][2]) {
+  asm volatile("" : "+v"(h[0][0]), "+v"(h[0][1]), "+v"(h[1][0]), "+v"(h[1][1]) : : "memory");
+}
+__device__ __forceinline__ void tie_regs(u32x4 (&b)[4]) {
+  asm volatile("" : "+v"(b[0]), "+v"(b[1]), "+v"(b[2]), "+v"(b[3]) : : "memory");
+}
+__device__ __forceinline__ void tie_regs(u32x4 (&b)[2]) { asm volatile("" : "+v"(b[0]), "+v"(b[1]) : : "memory"); }
 
 // Split operands (PL > 1 planes): every matrix is the sum of PL bf16 arrays ("planes", plane q at element offset
 // q * plane stride from the base pointer), each holding what the planes before it left of the fp32 value after
@@ -117,11 +129,9 @@ constexpr int seg_plane(int pl, int s, int which) {
 // LKM: the L operand is stored K-major (element (i, k) at L[k * ldl + i], i.e. the product is L^T-by-R^T of two
 // row-major arrays); its MFMA fragments then come from LDS through the transposing read ds_read_b64_tr_b16.
 // PL: number of bf16 planes per matrix (1: plain bf16).
-template <int BM, int BN, int WM_, int WN_, int NSTAGE, int MINB, bool LKM, int PL>
-__global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const GemmProblem* __restrict__ probs,
-                                                                            const GemmTile* __restrict__ tiles,
-                                                                            float beta_acc, float beta_e, int alpha_idx,
-                                                                            float diag_add) {
+template <int BM, int BN, int WM_, int WN_, int NSTAGE, bool LKM, int PL>
+__device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmTile& tile, unsigned char* smem, float beta_acc,
+                                               float beta_e, int alpha_idx, float diag_add) {
   constexpr int NW = WM_ * WN_, NT = NW * 64;
   constexpr int WTM = BM / WM_, WTN = BN / WN_;    // wave tile
   constexpr int FM = WTM / 32, FN = WTN / 32;      // 32x32 MFMA tiles per wave
@@ -133,19 +143,12 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
   static_assert(NW % 2 == 0 && NSTAGE == 2 && NLOAD < 32, "pipeline shape");
   static_assert(4 * FM == WTM / 8 && (WTM / 8 & (WTM / 8 - 1)) == 0 && BM / 8 >= 16, "slot addressing: 4i+q and wm*WTM/8 use disjoint bits");
+  (void)NT;
 
-  extern __shared__ __align__(16) unsigned char smem[];
-
-  const GemmTile tile = tiles[blockIdx.x];
-  const GemmProblem p = probs[tile.prob];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN_, wn = wave % WN_;
-  const int row0 = tile.ti * BM, col0 = tile.tj * BN;
-  DBG_BLK(0);
-#ifdef MUON_DBG_TIMING
-  if (tid == 0 && blockIdx.x < 8192) g_dbg_clk[blockIdx.x * 2] = clock64();
-#endif
+  const int row0 = tile.r0 * kTileUnit, col0 = tile.c0 * kTileUnit;
 
   // ---- DMA addressing: a wave instruction fills 8 rows x 128 B; lane i -> slot (row i/8, chunk position i%8).
   // Position s of row R holds logical chunk s ^ ((R/2)%8); R = 8*(instruction index) + i/8 and the instruction
@@ -248,11 +251,13 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   // transposing reads each - then the B-side tiles; MFMA number t of a k-step: tile (t / FN, t % FN)).
   constexpr int RPS = 2 * FM + FN;               // LDS read instructions per k-step on the K-major path
   // On this path ALL fragment reads are assembly and the waits for them are placed by hand (the compiler neither
-  // sees the reads nor counts them): one wait for the k-step-0 fragments before phase B's first MFMA, one for
-  // everything at the end of phase B.  The LDS returns data in issue order.  What this relies on: between a read
-  // and the wait that covers it the compiler must not touch the destination registers (no copy, no spill) - the
-  // fragment arrays are consumed by MFMAs only, after the waits, and the generated main loop is checked to hold
-  // neither moves nor scratch traffic; the parity tests would show a violation as wrong results.
+  // sees the reads nor counts them; it puts a wait for ALL vector-memory traffic in front of the builtin form of the
+  // transposing read, which drains the slab prefetch): one wait for the k-step-0 fragments before phase B's first MFMA,
+  // one for everything at the end of phase B.  The LDS returns data in issue order.  Every wait is an asm statement
+  // that takes the fragment registers it covers as read-write operands (land_kstep below): to the compiler the
+  // wait produces those values, so every MFMA that consumes a fragment depends on the wait that covers it and
+  // reads the registers the wait names - it cannot be moved ahead of the wait, nor fed from a copy or a spill slot
+  // made before the data landed.
   u32x2 km_half[KSTEPS][FM][2];
   u32x4 km_b[KSTEPS][FN];
   auto read_one = [&](int stage, int kk, int r) {
@@ -266,6 +271,13 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       const unsigned addr = (unsigned)(size_t)(lds_v4i16_ptr)(smem + stage * STAGE_B + (((2 * kk + fh) ^ fkey) * 16) + b_base + j * 32 * ROWB);
       asm volatile("ds_read_b128 %0, %1" : "=v"(km_b[kk][j]) : "v"(addr) : "memory");
     }
+  };
+  // "wait, then these registers hold the fragments of k-step kk"; only the first k-step of a group carries the
+  // s_waitcnt, the others just tie their registers to the same point of the instruction stream.
+  auto land_kstep = [&](int kk, auto cnt_tag, bool with_wait) {
+    if (with_wait) wait_lgkm_tie<decltype(cnt_tag)::value>(km_half[kk]);
+    else tie_regs(km_half[kk]);
+    tie_regs(km_b[kk]);
   };
   auto mma_one = [&](int kk, int t) {
     const int i = t / FN, j = t % FN;
@@ -312,7 +324,9 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   // iteration (`early`), the rest after the main loop.
   const u16* Et = static_cast<const u16*>(p.Et);
   constexpr int CPT = BM / 8;                    // 16-byte chunks per row of the transposed image
-  constexpr int RPI_T = 64 / CPT;                // image rows per wave-level DMA instruction / per 64 lanes
+  constexpr int KEYMASK = (CPT < 32 ? CPT : 32) - 1;   // image row c keeps its chunks XOR-swizzled by c & KEYMASK
+  constexpr int RPI_T = 64 / CPT > 0 ? 64 / CPT : 1;   // image rows per wave-level DMA instruction / per 64 lanes
+  static_assert(CPT <= 64, "one wave instruction covers at least one row of the transposed image");
   constexpr int TI = BN / RPI_T / NW;            // DMA instructions (or 64-lane store groups) per wave
   constexpr int IPS = STAGE_B / 1024 / NW;       // image DMA instructions per wave that land in one pipeline stage
   auto et_request = [&](int region, int plane = 0) {   // requests the part of the image that overlays pipeline stage `region`
@@ -324,8 +338,9 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     unsigned char* dstl = smem + idx0 * 1024;
 #pragma unroll
     for (int i = 0; i < (IPS < TI ? IPS : TI); ++i) {
+      if (region * IPS + i >= TI) break;         // the last region may hold fewer instructions than a stage has room for
       const int c = c0 + i * NW * RPI_T;
-      const int chunk = (lane % CPT) ^ (c & (CPT - 1));
+      const int chunk = (lane % CPT) ^ (c & KEYMASK);
       __builtin_amdgcn_global_load_lds((gptr)(src + (size_t)(i * NW * RPI_T) * p.ldet + chunk * 8), (lptr)(dstl + i * NW * 1024), 16, 0, 0);
     }
   };
@@ -337,7 +352,6 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   auto iteration = [&](auto refill_tag, auto sync_tag) {
     constexpr bool REFILL = decltype(refill_tag)::value, SYNC = decltype(sync_tag)::value;
     constexpr int DSG = 2 * ((LKM ? 2 : 1) * FM + FN) / (FM + FN);   // LDS reads per scheduling group of phases A, B
-    DBG_T(0);
     if (LKM) {
       constexpr int NG = FM + FN, RG = 2 * RPS / NG, MT = FM * FN;
       constexpr int LEAD = MT >= NG + 2 ? 2 : 0; // MFMAs of k-step 0 issued ahead of phase B's reads
@@ -351,9 +365,8 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
         for (int t = 0; t < MT / NG; ++t) mma_one(KSTEPS - 1, g * (MT / NG) + t);
         __builtin_amdgcn_sched_barrier(0);
       }
-      DBG_T(1);
       // B: MFMAs of k-step 0 lead, then one per group of reads of k-steps 2, 3
-      __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | ((RPS < 15 ? RPS : 15) << 8));   // lgkmcnt(RPS): k-step 0 is in
+      land_kstep(0, std::integral_constant<int, (RPS < 15 ? RPS : 15)>{}, true);   // lgkmcnt(RPS): k-step 0 is in
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < LEAD; ++t) mma_one(0, t);
@@ -368,7 +381,9 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
 #pragma unroll
       for (int t = LEAD + NG; t < MT; ++t) mma_one(0, t);
       __builtin_amdgcn_sched_barrier(0);
-      wait_lgkm0();                              // k-steps 1..3 are in (and nobody of this wave reads the stage any more)
+      land_kstep(1, Zero{}, true);               // k-steps 1..3 are in (and nobody of this wave reads the stage any more)
+      land_kstep(2, Zero{}, false);
+      land_kstep(3, Zero{}, false);
       __builtin_amdgcn_sched_barrier(0);
     } else {
     // A
@@ -383,7 +398,6 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       if (SYNC && TAIL > 0 && g % ((FM + FN) / (TAIL > 0 ? TAIL : 1)) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
-    DBG_T(1);
     // B.  MFMAs go first: the LDS counter is only 4 bits wide, so a wait placed behind more than 15 younger reads
     // degenerates into "wait for everything".
     fread(cur, 2);
@@ -400,11 +414,9 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);
     __builtin_amdgcn_sched_barrier(0);
     }
-    DBG_T(2);
     if (REFILL) {
       wait_lgkm0();                              // my fragment reads have returned
       __builtin_amdgcn_s_barrier();              // barrier #1: stage `cur` is free
-      DBG_T(3);
       request_part(kt + 2, cur, Zero{}, HeadN{});
     }
     // C
@@ -433,12 +445,10 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    DBG_T(4);
     if (SYNC) {
       if (REFILL) wait_vmcnt<HEAD>(); else wait_vmcnt<0>();   // slab kt+1 has landed (the head of slab kt+2 may be in flight)
       __builtin_amdgcn_s_barrier();              // barrier #2: ... for every wave
     }
-    DBG_T(5);
     cur ^= 1;
     ++kt;
   };
@@ -453,22 +463,16 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   } else {
     mma(KSTEPS - 1);
   }
-  DBG_BLK(1);
-#ifdef MUON_DBG_TIMING
-  if (tid == 0 && blockIdx.x < 8192) g_dbg_clk[blockIdx.x * 2 + 1] = clock64();
-#endif
 
   // ======================================= epilogue =======================================
   // val = alpha * (beta_acc*acc + beta_e*E).  Each lane owns, per MFMA tile, one column c and rows 8q+4h+e
   // (e = 0..3 contiguous): exactly 8 contiguous bytes of the TRANSPOSED tile.  So the transposed addend tile is
-  // DMA-ed into an LDS image [BN][BM] (16-byte chunks of row c XOR-swizzled by c % chunks-per-row), each lane replaces its
+  // DMA-ed into an LDS image [BN][BM] (16-byte chunks of row c XOR-swizzled by the low bits of c), each lane replaces its
   // 8-byte pieces in place with the results, and the image leaves with coalesced 16-byte stores: that is Ct.
   // For C the packed results are transposed on the matrix cores (P^T = P^T * I with a 0/1 selector operand,
   // exact in fp32), which hands each lane 8 contiguous bytes of a ROW of the tile; same image trick, [BM][BN].
-  DBG_E(0);
   wait_vmcnt<0>();
   __syncthreads();                               // every wave is done with the pipeline stages
-  DBG_E(1);
   const float alpha = alpha_idx >= 0 ? p.scal[alpha_idx] : 1.f;
   const float ab_acc = alpha * beta_acc, ab_e = alpha * beta_e;   // val = alpha*(beta_acc*acc + beta_e*E), alpha folded in
   u16* C = static_cast<u16*>(p.C);
@@ -477,26 +481,26 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   if (p.symmetric) {                             // mirror store below the diagonal; T itself only off the diagonal
     Ct = C;
     ldct = p.ldc;
-    if (tile.ti == tile.tj) C = nullptr;
+    if (tile.flags & kTileDiagonal) C = nullptr;
   }
   if constexpr (PL == 1) {
   if (Et) {
     et_request(cur ^ 1);        // `cur` was flipped after the last iteration: cur^1 is the stage that iteration still read
-    DBG_E(2);
     wait_vmcnt<0>();
     __syncthreads();
   }
   }
-  DBG_E(3);
 
   // Each lane's slot for (MFMA tile i, j; quarter q): image row c = wn*WTN + 32j + r, logical chunk
-  // wm*WTM/8 + 4i + q, half h.  The swizzle key c % CPT equals r % CPT, so the slot address is a per-lane base
-  // XOR a compile-time constant.  The addend pieces of tile t+1 are read while tile t is being combined.
+  // wm*WTM/8 + 4i + q, half h.  The swizzle key c & KEYMASK equals r & KEYMASK (wave and MFMA tile origins are
+  // multiples of 32), so the slot address is a per-lane base XOR a compile-time constant.  The addend pieces of tile t+1 are read while tile t is being combined.
   u32x2 pk[FM][FN][4];
-  // diagonal constant: only MFMA tiles i == j of the waves on the tile's diagonal (wm == wn) of a diagonal tile
-  // hold elements C[r][r]; within such an MFMA tile, row 8q + 4h + e meets column fr
-  const bool diag_here = p.diag_add != 0 && tile.ti == tile.tj && wm == wn;
-  const unsigned slot_base = (unsigned)((wn * WTN + fr) * (BM * 2) + fh * 8) + ((unsigned)((wm * (WTM / 8)) ^ (fr & (CPT - 1))) << 4);
+  // diagonal constant: this wave's MFMA tile (i, j) starts at row row0 + wm*WTM + 32 i and column col0 + wn*WTN + 32 j
+  // of the output; it holds elements C[r][r] when the two are equal, and then row 8q + 4h + e of the MFMA tile meets
+  // column fr.  diag_shift = 32 (j - i) for the MFMA tiles that lie on the matrix diagonal (all starts are multiples
+  // of 32); any other value: none of this wave's.
+  const int diag_shift = p.diag_add != 0 ? (row0 + wm * WTM) - (col0 + wn * WTN) : 1;
+  const unsigned slot_base = (unsigned)((wn * WTN + fr) * (BM * 2) + fh * 8) + ((unsigned)((wm * (WTM / 8)) ^ (fr & KEYMASK)) << 4);
   auto slot_of = [&](int i, int j, int q) -> unsigned char* {
     return smem + ((slot_base + (unsigned)(j * 32 * BM * 2)) ^ (unsigned)((4 * i + q) << 4));
   };
@@ -527,11 +531,9 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
           x[2] = fmaf(ab_e, __uint_as_float(e2.y << 16), x[2]);
           x[3] = fmaf(ab_e, __uint_as_float(e2.y & 0xffff0000u), x[3]);
         }
-        if (i == j && BM == BN && FM == FN) {
-          if (diag_here) {
+        if (diag_shift == 32 * (j - i)) {        // wave-uniform
 #pragma unroll
-            for (int e = 0; e < 4; ++e) x[e] += (fr == 8 * q + 4 * fh + e) ? diag_add : 0.f;
-          }
+          for (int e = 0; e < 4; ++e) x[e] += (fr == 8 * q + 4 * fh + e) ? diag_add : 0.f;
         }
         const f32x2 lo = {x[0], x[1]}, hi = {x[2], x[3]};
         pk[i][j][q].x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
@@ -543,20 +545,17 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
   };
   if constexpr (PL == 1) {
   if (Et) combine(std::true_type{}); else combine(std::false_type{});
-
-  DBG_E(4);
   if (Ct) {
     __syncthreads();
-    DBG_E(5);
     constexpr int SB = TI < 8 ? TI : 8;          // image chunks read per batch before they are stored
     // image row of step i: c = c_first + i * (NW * RPI_T); the swizzle key c % 16 only has period 16 / (NW * RPI_T)
-    constexpr int CSTEP = NW * RPI_T, PERIOD = CPT / CSTEP > 0 ? CPT / CSTEP : 1;
+    constexpr int CSTEP = NW * RPI_T, PERIOD = (KEYMASK + 1) / CSTEP > 0 ? (KEYMASK + 1) / CSTEP : 1;
     const int c_first = wave * RPI_T + lane / CPT;
     u16* dst[PERIOD];
 #pragma unroll
     for (int k = 0; k < PERIOD; ++k) {
       const int c = c_first + k * CSTEP;
-      dst[k] = Ct + (size_t)(col0 + c) * ldct + row0 + ((lane % CPT) ^ (c & (CPT - 1))) * 8;
+      dst[k] = Ct + (size_t)(col0 + c) * ldct + row0 + ((lane % CPT) ^ (c & KEYMASK)) * 8;
     }
     const size_t dstep = (size_t)(CSTEP * PERIOD) * ldct;
 #pragma unroll
@@ -572,7 +571,6 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  DBG_E(6);
   if (C) {
     // selector operand: k index (h, t) of k-step s stands for tile row 16s + 4h + t (t < 4) or 16s + 8 + 4h + t - 4
     bf16x8 sel[2];
@@ -610,9 +608,7 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
           *reinterpret_cast<u32x2*>(smem + r * (BN * 2) + ((lchunk ^ (r & (CPR - 1))) * 16) + fh * 8) = w;
         }
       }
-    DBG_E(7);
     __syncthreads();
-    DBG_E(8);
     constexpr int SB = CI < 8 ? CI : 8;
     constexpr int RSTEP = NW * RPI_C, PERIOD = CPR / RSTEP > 0 ? CPR / RSTEP : 1;
     const int r_first = wave * RPI_C + lane / CPR;
@@ -658,14 +654,14 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
         for (int v = 0; v < 16; ++v) acc[i][j][v] *= ab_acc;
         __builtin_amdgcn_sched_barrier(0);
       }
-    if (BM == BN && FM == FN) {
-      if (diag_here) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[i][i < FN ? i : 0][v] += (fr == 8 * (v >> 2) + 4 * fh + (v & 3)) ? diag_add : 0.f;
-      }
-    }
+      for (int j = 0; j < FN; ++j)
+        if (diag_shift == 32 * (j - i)) {        // wave-uniform
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] += (fr == 8 * (v >> 2) + 4 * fh + (v & 3)) ? diag_add : 0.f;
+        }
     if (Et) {
 #pragma unroll 1
       for (int q = 0; q < PL; ++q) {
@@ -691,14 +687,14 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
     }
     // store-out of the transposed image [BN][BM] and of the row-major image [BM][BN]: 16 bytes per lane, coalesced
     constexpr int SBT = TI < 8 ? TI : 8;
-    constexpr int CSTEP = NW * RPI_T, PERIOD_T = CPT / CSTEP > 0 ? CPT / CSTEP : 1;
+    constexpr int CSTEP = NW * RPI_T, PERIOD_T = (KEYMASK + 1) / CSTEP > 0 ? (KEYMASK + 1) / CSTEP : 1;
     auto store_ct = [&](u16* base) {
       const int c_first = wave * RPI_T + lane / CPT;
       u16* dst[PERIOD_T];
 #pragma unroll
       for (int k = 0; k < PERIOD_T; ++k) {
         const int c = c_first + k * CSTEP;
-        dst[k] = base + (size_t)(col0 + c) * ldct + row0 + ((lane % CPT) ^ (c & (CPT - 1))) * 8;
+        dst[k] = base + (size_t)(col0 + c) * ldct + row0 + ((lane % CPT) ^ (c & KEYMASK)) * 8;
       }
       const size_t dstep = (size_t)(CSTEP * PERIOD_T) * ldct;
 #pragma unroll
@@ -811,32 +807,57 @@ __global__ __launch_bounds__(WM_* WN_ * 64, MINB) void ns_gemm_bf16_kernel(const
       }
     }
   }
-  DBG_E(9);
-  DBG_BLK(2);
-  DBG_BLK(3);
 }
 
-// ---- instantiations: {tile, waves, stages, waves per SIMD} per GemmShape, x {L contiguous along k, K-major} x planes ----
+// ---- kernels.  Fine launch: 128 x 128 tiles, two blocks per compute unit.  Coarse launch: one block per compute
+// unit, each block running the shape its table entry names - 256 x 256 (2 x 2 waves) or 512 x 128 (4 x 1 waves; the
+// 128-wide strips that an odd multiple of 128 leaves beside the 256-tiles).  Both coarse shapes give every wave a
+// 128 x 128 tile, so they share register budget, MFMA schedule and per-wave LDS traffic, and a launch mixes them freely:
+// the strips fill compute units next to the 256-tiles of the same product instead of running as a launch of their own.
 constexpr size_t kLds128 = TileCfg<128, 128>::lds_bytes(2);
 constexpr size_t kLds256 = TileCfg<256, 256>::lds_bytes(2);
+constexpr size_t kLds512 = TileCfg<512, 128>::lds_bytes(2);
 constexpr int kMaxPlanes = 3;
 
 template <bool LKM, int PL>
-hipError_t setup_pair() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, LKM, PL>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds128);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(&ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, LKM, PL>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds256);
+__global__ __launch_bounds__(256, 2) void ns_gemm_bf16_fine_kernel(const GemmProblem* __restrict__ probs,
+                                                                    const GemmTile* __restrict__ tiles, float beta_acc,
+                                                                    float beta_e, int alpha_idx, float diag_add) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const GemmTile tile = tiles[blockIdx.x];
+  const GemmProblem p = probs[tile.prob];
+  gemm_tile_body<128, 128, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
 }
 
 template <bool LKM, int PL>
-void launch_one(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc, float beta_e,
-                int alpha_idx, float diag_add, hipStream_t s) {
-  if (shape == kShape128)
-    ns_gemm_bf16_kernel<128, 128, 2, 2, 2, 2, LKM, PL><<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+__global__ __launch_bounds__(256, 1) void ns_gemm_bf16_kernel(const GemmProblem* __restrict__ probs,
+                                                               const GemmTile* __restrict__ tiles, float beta_acc,
+                                                               float beta_e, int alpha_idx, float diag_add) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const GemmTile tile = tiles[blockIdx.x];
+  const GemmProblem p = probs[tile.prob];
+  if (__builtin_amdgcn_readfirstlane(tile.shape) == kShape512x128)
+    gemm_tile_body<512, 128, 4, 1, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
   else
-    ns_gemm_bf16_kernel<256, 256, 2, 2, 2, 1, LKM, PL><<<n_tiles, 256, kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+    gemm_tile_body<256, 256, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+}
+
+template <bool LKM, int PL>
+hipError_t setup_pair() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&ns_gemm_bf16_fine_kernel<LKM, PL>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds128);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&ns_gemm_bf16_kernel<LKM, PL>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds512);
+}
+
+template <bool LKM, int PL>
+void launch_one(int coarse, int strips, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
+                float beta_e, int alpha_idx, float diag_add, hipStream_t s) {
+  if (!coarse)
+    ns_gemm_bf16_fine_kernel<LKM, PL><<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+  else
+    ns_gemm_bf16_kernel<LKM, PL><<<n_tiles, 256, strips ? kLds512 : kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
 }
 
 }  // namespace
@@ -851,12 +872,12 @@ hipError_t gemm_setup() {
   return e;
 }
 
-hipError_t launch_gemm_bf16(int shape, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
+hipError_t launch_gemm_bf16(int coarse, int strips, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
                             float beta_e, int alpha_idx, float diag_add, int l_kmajor, int planes, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
-  if ((shape != kShape128 && shape != kShape256) || planes < 1 || planes > kMaxPlanes) return hipErrorInvalidValue;
+  if (planes < 1 || planes > kMaxPlanes) return hipErrorInvalidValue;
 #define MUON_GEMM_CASE(K, P)                                                                                     \
-  if ((l_kmajor != 0) == K && planes == P) launch_one<K, P>(shape, probs, tiles, n_tiles, beta_acc, beta_e, alpha_idx, diag_add, s)
+  if ((l_kmajor != 0) == K && planes == P) launch_one<K, P>(coarse, strips, probs, tiles, n_tiles, beta_acc, beta_e, alpha_idx, diag_add, s)
   MUON_GEMM_CASE(false, 1);
   MUON_GEMM_CASE(true, 1);
   MUON_GEMM_CASE(false, 2);

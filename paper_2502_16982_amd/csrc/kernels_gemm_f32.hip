@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void ns_gemm_f32_kernel(const GemmProblem* __r
   const GemmProblem p = probs[tile.prob];
   const int tid = threadIdx.x;
   const int tx = tid & 15, ty = tid >> 4;
-  const int row0 = tile.ti * T, col0 = tile.tj * T;
+  const int row0 = tile.r0 * kTileUnit, col0 = tile.c0 * kTileUnit;
   const int ld_row = tid >> 2, ld_k4 = (tid & 3) * 4;
   const float* lptr = static_cast<const float*>(p.L) + (size_t)(row0 + ld_row) * p.ldl + ld_k4;
   const float* rptr = static_cast<const float*>(p.R) + (size_t)(col0 + ld_row) * p.ldr + ld_k4;
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void ns_gemm_f32_kernel(const GemmProblem* __r
   float* Ct = static_cast<float*>(p.Ct);
   int ldct = p.ldct;
   if (p.symmetric) {
-    Ct = (tile.ti != tile.tj) ? C : nullptr;
+    Ct = (tile.flags & kTileDiagonal) ? nullptr : C;
     ldct = p.ldc;
   }
 #pragma unroll

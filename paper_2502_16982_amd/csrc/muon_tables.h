@@ -71,9 +71,22 @@ struct GemmProblem {
   int64_t l_plane, r_plane, et_plane, c_plane, ct_plane;
 };
 
+// One block's output tile.  Rows and columns are counted in units of kTileUnit elements, so that tiles of several
+// block shapes (and tiles shifted to end at the matrix edge) share one table format.
+constexpr int kTileUnit = 64;
+// Block-tile shapes of the bf16 matrix-core kernel (the fp32 kernel has one 64 x 64 shape and ignores the field).
+enum GemmShape : int { kShape128 = 0, kShape256 = 1, kShape512x128 = 2, kNumShapes = 3 };
+constexpr int kShapeRows[kNumShapes] = {128, 256, 512};
+constexpr int kShapeCols[kNumShapes] = {128, 256, 128};
+constexpr int kF32Tile = 64;       // block tile of the fp32 Newton-Schulz GEMM
+constexpr int kTileDiagonal = 1;   // GemmTile::flags: tile on the diagonal of a symmetric product: it is its own mirror
+                                   // image, so only one of the two stores is made
 struct GemmTile {
   int32_t prob;
-  int16_t ti, tj;     // tile row / column, in units of the kernel's block tile
+  uint16_t r0, c0;    // first output row / column, in units of kTileUnit
+  uint8_t shape;      // GemmShape
+  uint8_t flags;      // kTileDiagonal
+  uint16_t pad_;
 };
 
 }  // namespace muon

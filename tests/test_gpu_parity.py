@@ -28,6 +28,8 @@ def assert_records(recs, tol_fro):
         print(r, flush=True)
         assert r["o_finite"], r
         assert r["o_rel_fro"] <= tol_fro, r
+        assert r["o_blk_max"] <= U.BLOCK_FACTOR * tol_fro, r
+        assert r["o_elem_max"] <= U.ELEM_FACTOR * tol_fro, r
         assert r["m_err"] <= U.TOL_ELEM, r
         w = r["w"]
         if "max_rel" in w:
@@ -85,16 +87,26 @@ def test_bf16_outliers(dev):
     assert_records(U.run_and_compare(wl, dev), U.TOL_BF16_FRO)
 
 
-@pytest.mark.parametrize("ns_steps", [0, 1, 2, 10])
+@pytest.mark.parametrize("ns_steps", [0, 1, 2, 5, 10])
 def test_ns_step_counts(dev, ns_steps):
-    wl = workloads.custom("steps", [(192, 320), (320, 192)], seed_base=25)
-    recs = U.run_and_compare(wl, dev, hp_over={"ns_steps": ns_steps})
-    # the quintic is expansive around its fixed point (|f'(0.868)| = 1.58), so bf16 rounding noise grows with
-    # the iteration count: the 2e-2 bound is stated for N <= 5; N = 10 gets 5e-2
-    assert_records(recs, {0: 5e-3, 10: 5e-2}.get(ns_steps, U.TOL_BF16_FRO))
     wl32 = workloads.custom("steps32", [(96, 160), (160, 96)], w_dtype=torch.float32, g_dtype=torch.float32, ns_dtype="f32",
                             w_std=1.0, g_std=1.0, seed_base=26)
     assert_records(U.run_and_compare(wl32, dev, hp_over={"ns_steps": ns_steps}), U.TOL_F32_FRO)
+    wl = workloads.custom("steps", [(192, 320), (320, 192)], seed_base=25)
+    recs = U.run_and_compare(wl, dev, hp_over={"ns_steps": ns_steps})
+    if ns_steps == 10:
+        # Known gap of the plain bf16 arithmetic, stated in include/muon.h: the 2e-2 bar holds for N <= 5.  The quintic
+        # is expansive around its fixed point (|f'(0.868)| = 1.58), so bf16 rounding noise keeps growing with the
+        # iteration count: measured 2.2-2.3e-2 here.  The run must still be sane (finite, within 5e-2); the parity
+        # claim for N = 10 is made by MUON_BF16X2 (test_split_step_counts) and fails here by design.
+        for r in recs:
+            print(r, flush=True)
+            assert r["o_finite"] and r["o_rel_fro"] <= 5e-2 and r["m_err"] <= U.TOL_ELEM, r
+        if max(r["o_rel_fro"] for r in recs) > U.TOL_BF16_FRO:
+            pytest.xfail("plain bf16 Newton-Schulz at N = 10 misses the 2e-2 bar (%.2e): documented range is N <= 5"
+                         % max(r["o_rel_fro"] for r in recs))
+        return
+    assert_records(recs, 5e-3 if ns_steps == 0 else U.TOL_BF16_FRO)
 
 
 def test_other_coefficients_and_hyperparameters(dev):
@@ -275,13 +287,17 @@ def test_largest_dimensions(dev, ns):
     range, K loops of 16384 slabs.  Gaussian gradient except for three 64-wide bands (first, middle and last K slab of
     the Gram product) scaled by 128, each carrying as much energy as all the rest, so that a slab dropped or read twice
     where a boundary could go wrong moves O by tens of percent.  Four equal singular values make the relative error of
-    O that of ONE number, which the five iterations amplify about 5 times (nothing averages out): the bars are widened
-    to 1e-1 (bf16; an emulation of ideal bf16 storage on Gaussian 4 x 2^20 gives 3e-2) and 3e-4 (two planes; emulation
-    5e-5, measured 0.8-1.1e-4); the fp32 path keeps 1e-4.  (Inputs with only a few distinct values are another matter
+    O that of ONE number, which the five iterations amplify about 5 times (nothing averages out): an emulation of ideal
+    bf16 storage on Gaussian 4 x 2^20 gives 3e-2, of two planes 5e-5.  The test therefore asserts a structural bound
+    (1e-1 bf16, 3e-4 two planes) and reports the case as an expected failure when the parity bar of the arithmetic
+    (2e-2, 1e-4) is missed - the documented range of MUON_BF16 / MUON_BF16X2 excludes it; the fp32 path keeps 1e-4.  (Inputs with only a few distinct values are another matter
     at this length: a matrix-core accumulator is one chain of K / 16 fp32 additions whose rounding errors then all
     point the same way - 1e-2 in O for a +-2^-10 sign matrix with two or three planes alike.)"""
     big = 1 << 20
-    tol = {"bf16": 1e-1, "bf16x2": 3e-4, "f32": U.TOL_F32_FRO}[ns]
+    # structural bound (a dropped or doubled slab moves O by tens of percent) and the parity bar of the arithmetic
+    sane = {"bf16": 1e-1, "bf16x2": 3e-4, "f32": U.TOL_F32_FRO}[ns]
+    bar = {"bf16": U.TOL_BF16_FRO, "bf16x2": U.TOL_SPLIT_FRO["bf16x2"], "f32": U.TOL_F32_FRO}[ns]
+    worst = 0.0
     for shape in ((4, big), (big, 4)):
         gen = torch.Generator(device=dev).manual_seed(62 + shape[0] % 7)
         g = torch.randn(shape, generator=gen, device=dev) * 1e-3
@@ -299,12 +315,130 @@ def test_largest_dimensions(dev, ns):
         W, M, O = U.oracle_step(w0, g0, np.zeros(shape), d)
         o_gpu = U.to64(st.read_update(0))
         err = U.rel_fro(o_gpu, O)
+        worst = max(worst, err)
         print({"ns": ns, "shape": shape, "o_rel_fro": err}, flush=True)
         assert torch.equal(m, g.float())
-        assert err <= tol, (shape, err)
+        assert err <= sane, (shape, err)
         chk = U.check_weight_update(w, w0, o_gpu, d)
         assert chk["max_excess"] <= 1.0 and chk["frac_off"] <= 2e-3, chk
         st.close()
+    if worst > bar:
+        # Known gap, stated in include/muon.h: with a handful of rows and K = 2^20 nothing averages out (see above);
+        # measured 2.2-2.9e-2 (bf16) and 0.8-1.1e-4 (two planes) against bars of 2e-2 and 1e-4.
+        pytest.xfail("4 x 2^20 with %s: %.2e exceeds the %.0e bar of the arithmetic (documented range)" % (ns, worst, bar))
+
+
+def _structured_cases():
+    """Matrices the method treats specially (Newton-Schulz acts on singular values only, section 2.1): fed as the
+    gradient with zero momentum, so that U is the matrix itself up to the factor 1 + mu."""
+    rng = np.random.default_rng(71)
+    cases = {}
+    q, _ = np.linalg.qr(rng.standard_normal((1024, 256)))
+    cases["orthonormal_rows_256x1024"] = q.T                              # all singular values equal
+    cases["orthonormal_cols_1024x256"] = q
+    cases["diagonal_256"] = np.diag(np.geomspace(1e-3, 1.0, 256) * np.where(np.arange(256) % 3 == 0, -1.0, 1.0))
+    cases["identical_rows_192x320"] = np.tile(rng.standard_normal((1, 320)), (192, 1))          # rank 1
+    cases["rank_deficient_256x384"] = rng.standard_normal((256, 96)) @ rng.standard_normal((96, 384))   # rank 96 of 256
+    return cases
+
+
+@pytest.mark.parametrize("ns", ["bf16", "bf16x2", "f32"])
+@pytest.mark.parametrize("case", ["orthonormal_rows_256x1024", "orthonormal_cols_1024x256", "diagonal_256",
+                                  "identical_rows_192x320", "rank_deficient_256x384"])
+def test_structured_inputs(dev, ns, case):
+    """Equal singular values, a diagonal matrix, rank one and rank deficiency, through every arithmetic.
+    Rank-deficient inputs have exact zeros among their singular values, which the quintic amplifies 3.4445-fold per
+    iteration: whatever a path's rounding (2^-9 bf16 storage, 2^-17 two planes, 2^-21 fp32 accumulation) puts into the null
+    space grows up to 485-fold in five iterations.  For them O is therefore compared on the row and column space of
+    the input at the path's bar, and the null-space part is checked against that amplification bound."""
+    mat = _structured_cases()[case]
+    tol = {"bf16": U.TOL_BF16_FRO, "bf16x2": U.TOL_SPLIT_FRO["bf16x2"], "f32": U.TOL_F32_FRO}[ns]
+    g = torch.tensor(mat, dtype=torch.float32, device=dev).contiguous()
+    w = torch.zeros_like(g)
+    m = torch.zeros_like(g)
+    g64 = U.to64(g)
+    hp, d = U.hp_from(workloads.Hyper(), lr=0.02, weight_decay=0.0, eps=0.0)
+    st = binding.MuonStepper([(w, g, m)], ns_dtype=ns)
+    st.step(hp)
+    torch.cuda.synchronize()
+    W, M, O = U.oracle_step(np.zeros_like(g64), g64, np.zeros_like(g64), d)
+    o_gpu = U.to64(st.read_update(0))
+    st.close()
+    assert np.isfinite(o_gpu).all()
+    assert U.momentum_error(U.to64(m), M, np.zeros_like(g64), g64, d["momentum"]) <= U.TOL_ELEM
+    low_rank = case.startswith(("identical_rows", "rank_deficient"))
+    if not low_rank:
+        err = U.rel_fro(o_gpu, O)
+        print({"case": case, "ns": ns, "o_rel_fro": err, **U.block_errors(o_gpu, O)}, flush=True)
+        assert err <= tol, (case, ns, err)
+        if case.startswith("diagonal"):
+            off = o_gpu - np.diag(np.diag(o_gpu))
+            assert np.count_nonzero(off) == 0          # zeros stay exact zeros in every arithmetic
+        return
+    # projectors onto the row and column space of the input, from its SVD.  The input reaches both sides rounded to
+    # fp32, which fills its null space with singular values around 1e-7 of the largest: the oracle amplifies those
+    # to 5e-5 at most, so "rank" means the singular values above 1e-5 of the largest.
+    u, sv, vt = np.linalg.svd(g64, full_matrices=False)
+    r = int((sv > 1e-5 * sv[0]).sum())
+    assert r == {"identical_rows_192x320": 1, "rank_deficient_256x384": 96}[case]
+    pu, pv = u[:, :r] @ u[:, :r].T, vt[:r].T @ vt[:r]
+    inside = pu @ o_gpu @ pv
+    outside = (o_gpu - inside) - (O - pu @ O @ pv)      # beyond what the oracle itself has there (5e-5 of the fp32 input)
+    err_in = U.rel_fro(inside, pu @ O @ pv)
+    # relative noise an iteration puts into its iterate: storage rounding for the matrix-core paths (2^-9, 2^-17); for
+    # the fp32 path the fp32 accumulation of the products over K <= 1024 terms, about sqrt(K) 2^-24 <= 2^-21
+    storage = {"bf16": 2.0 ** -9, "bf16x2": 2.0 ** -17, "f32": 2.0 ** -21}[ns]
+    # ||outside||_F: the noise of the first iterate (Frobenius norm 1) is at most `storage` and grows
+    # 3.4445^5-fold; what later iterations inject grows less (sum of the geometric series: factor 1.41)
+    bound_out = 3.4445 ** 5 * storage * 1.5
+    print({"case": case, "ns": ns, "rank": r, "o_rel_fro_range": err_in, "null_norm": float(np.linalg.norm(outside)),
+           "null_bound": bound_out, "o_norm": float(np.linalg.norm(O))}, flush=True)
+    assert np.linalg.norm(outside) <= bound_out, (case, ns, float(np.linalg.norm(outside)), bound_out)
+    if ns == "bf16" and tol < err_in <= 5e-2:
+        # Known gap of the plain bf16 arithmetic, stated in include/muon.h: when all rows are multiples of one row,
+        # every rounding error repeats in every row and nothing averages out over the Gram product; a numpy model of
+        # the arithmetic gives 2.2e-2 for identical rows (1.4e-2 with the a X term kept as an fp32 addend).
+        pytest.xfail("bf16 Newton-Schulz on %s: %.2e on the range of the input exceeds 2e-2 (documented range)" % (case, err_in))
+    assert err_in <= tol, (case, ns, err_in)
+
+
+@pytest.mark.parametrize("ns", ["bf16", "bf16x2", "f32"])
+def test_momentum_zero_ignores_a_nonzero_buffer(dev, ns):
+    """mu = 0 makes M_t = G whatever M_{t-1} held (section 2.1's recurrence): a momentum buffer of garbage-sized values
+    must leave no trace, in M or in O."""
+    wl = workloads.custom("mu0_" + ns, [(192, 320), (320, 192)], ns_dtype=ns, seed_base=72)
+    tensors = workloads.make_all(wl, dev)
+    for _, _, m in tensors:
+        m.normal_(0.0, 50.0)
+    hp, d = U.hp_from(wl.hyper, momentum=0.0)
+    host = [[U.to64(t) for t in trip] for trip in tensors]
+    st = binding.MuonStepper(tensors, ns_dtype=ns)
+    st.step(hp)
+    torch.cuda.synchronize()
+    tol = {"bf16": U.TOL_BF16_FRO, "bf16x2": U.TOL_SPLIT_FRO["bf16x2"], "f32": U.TOL_F32_FRO}[ns]
+    for i, (w0, g0, m0) in enumerate(host):
+        assert torch.equal(tensors[i][2], tensors[i][1].float())
+        W, M, O = U.oracle_step(w0, g0, m0, d)
+        assert U.rel_fro(U.to64(st.read_update(i)), O) <= tol
+    st.close()
+
+
+@pytest.mark.parametrize("ns", ["bf16", "bf16x2", "f32"])
+@pytest.mark.parametrize("g_std", [1e-12, 1e8])
+@pytest.mark.parametrize("eps", [0.0, 1e-7])
+def test_gradient_scale_invariance(dev, ns, g_std, eps):
+    """X_0 = U / ||U||_F does not depend on the scale of U (section 2.1).  The library stores the un-normalised U in
+    the iteration's dtype and applies 1 / ||U||_F^2 and 1 / ||U||_F in the first Gram and apply epilogues, so both
+    the sum of squares and those factors must stay inside fp32: gradients of standard deviation 1e-12 and 1e+8, both
+    orientations, with the paper's formula (eps = 0) and with the default eps (which is not small against
+    ||U||_F = 1e-12 * sqrt(A B), so the oracle's O shrinks accordingly - same formula both sides)."""
+    tol = {"bf16": U.TOL_BF16_FRO, "bf16x2": U.TOL_SPLIT_FRO["bf16x2"], "f32": U.TOL_F32_FRO}[ns]
+    wl = workloads.custom("scale_%s_%g" % (ns, g_std), [(192, 320), (320, 192)], w_dtype=torch.float32, g_dtype=torch.float32,
+                          ns_dtype=ns, w_std=1.0, g_std=g_std, seed_base=73)
+    recs = U.run_and_compare(wl, dev, hp_over={"eps": eps})
+    for r in recs:
+        print(r, flush=True)
+        assert r["o_finite"] and r["o_rel_fro"] <= tol and r["m_err"] <= U.TOL_ELEM, r
 
 
 def test_lr_zero_leaves_weights_bitwise(dev):
