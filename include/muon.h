@@ -49,7 +49,8 @@ typedef enum {
   MUON_E_HIP = -5,                 /* a HIP runtime call failed (see muon_last_hip_error)              */
   MUON_E_NOT_RESIDENT = -6,        /* debug read of a matrix whose workspace has been reused           */
   MUON_E_MISALIGNED = -7,          /* a buffer pointer is not aligned to its element size              */
-  MUON_E_NO_MEMORY = -8            /* host memory for the plan or its tables could not be allocated    */
+  MUON_E_NO_MEMORY = -8,           /* host memory for the plan or its tables could not be allocated    */
+  MUON_E_STATIC_LIMIT = -9         /* muon_step_static: more matrices or more workspace than its limits */
 } muon_status;
 
 /* The three ways of controlling the update RMS compared in section 3.1; the update is
@@ -126,6 +127,26 @@ int muon_init(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t ns_dt
  */
 int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hparams* hp,
               void* hip_stream, float* update_rms_out);
+
+/*
+ * muon_step for callers that cannot allocate device memory - code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: one call does what muon_init + muon_step do, with the tables and Newton-Schulz
+ * temporaries in a fixed device array inside the library instead of a caller-provided workspace.  It calls no
+ * hipMalloc, hipFree, hipHostMalloc or event/stream creation.  Same arguments and results as muon_step (params carry
+ * the buffer pointers AND the shapes; ns_dtype as for muon_init), on the current device.
+ * Limits: n <= MUON_STATIC_MAX_MATRICES, and muon_workspace_bytes(params, n, ns_dtype, 0) <= MUON_STATIC_MAX_BYTES;
+ * beyond them the call does nothing and returns MUON_E_STATIC_LIMIT.  Every device the library has run this call on
+ * holds MUON_STATIC_MAX_BYTES of device memory until the process ends.
+ * All calls on one device share that array: calls that overlap in time on one device (two host threads, or two
+ * streams whose work is not ordered) race; calls on one stream, one after the other, are safe.  The array keeps the
+ * previous call's contents; nothing in it needs clearing (every temporary is written in full before it is read).
+ * When the shape list differs from the previous call's on this device the launch plan is rebuilt in host memory and
+ * its tables are uploaded, waiting for hip_stream twice; repeated calls with one shape list only enqueue kernels.
+ */
+#define MUON_STATIC_MAX_BYTES (64u << 20)
+#define MUON_STATIC_MAX_MATRICES 64
+int muon_step_static(const muon_param* params, int32_t n, int32_t ns_dtype, const muon_hparams* hp, void* hip_stream,
+                     float* update_rms_out);
 
 /*
  * Test hook: copies O_t of matrix `index`, as left by the last muon_step, into dst (device, rows x cols,

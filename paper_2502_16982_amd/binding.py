@@ -20,14 +20,14 @@ MUON_SCALE_ADJUSTED_LR, MUON_SCALE_BASELINE, MUON_SCALE_UPDATE_NORM = 0, 1, 2
 MUON_OK = 0
 STATUS_NAMES = {
     0: "MUON_OK", -1: "MUON_E_INVALID_ARG", -2: "MUON_E_UNSUPPORTED_DTYPE", -3: "MUON_E_SHAPE_MISMATCH",
-    -4: "MUON_E_WORKSPACE_TOO_SMALL", -5: "MUON_E_HIP", -6: "MUON_E_NOT_RESIDENT", -7: "MUON_E_MISALIGNED", -8: "MUON_E_NO_MEMORY",
+    -4: "MUON_E_WORKSPACE_TOO_SMALL", -5: "MUON_E_HIP", -6: "MUON_E_NOT_RESIDENT", -7: "MUON_E_MISALIGNED", -8: "MUON_E_NO_MEMORY", -9: "MUON_E_STATIC_LIMIT",
 }
 
 EXPORTS = (
     "muon_default_hparams", "muon_workspace_bytes", "muon_init", "muon_step", "muon_debug_read_update",
     "muon_plan_describe", "muon_plan_chunks", "muon_destroy", "muon_status_string", "muon_last_hip_error",
     "muon_profile_enable", "muon_profile_read", "muon_adamw_step", "muon_probe_mfma_rate",
-    "muon_plan_only", "muon_plan_tiles",
+    "muon_plan_only", "muon_plan_tiles", "muon_step_static",
 )
 PROF_NAMES = ("momentum_norm_cast", "norm_finalize", "gram", "poly", "apply_poly", "weight_update", "update_rms")
 
@@ -95,6 +95,8 @@ def lib() -> C.CDLL:
     L.muon_init.restype = C.c_int
     L.muon_step.argtypes = [C.c_void_p, P(muon_param), C.c_int32, P(muon_hparams), C.c_void_p, C.c_void_p]
     L.muon_step.restype = C.c_int
+    L.muon_step_static.argtypes = [P(muon_param), C.c_int32, C.c_int32, P(muon_hparams), C.c_void_p, C.c_void_p]
+    L.muon_step_static.restype = C.c_int
     L.muon_debug_read_update.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
     L.muon_debug_read_update.restype = C.c_int
     L.muon_plan_describe.argtypes = [C.c_void_p, C.c_int32, P(C.c_int64), C.c_int32]
@@ -196,6 +198,12 @@ def muon_init(params, n: int, ns_dtype: int, workspace_ptr: int, workspace_bytes
 
 def muon_step(ctx, params, n: int, hp: muon_hparams, stream_ptr: int = 0, update_rms_ptr: int = 0) -> None:
     _check(lib().muon_step(ctx, params, n, C.byref(hp), C.c_void_p(stream_ptr), C.c_void_p(update_rms_ptr)), "muon_step")
+
+
+def muon_step_static(params, n: int, ns_dtype: int, hp: muon_hparams, stream_ptr: int = 0, update_rms_ptr: int = 0) -> None:
+    """One step with the workspace inside the library (no device allocation anywhere in the call)."""
+    _check(lib().muon_step_static(params, n, ns_dtype, C.byref(hp), C.c_void_p(stream_ptr), C.c_void_p(update_rms_ptr)),
+           "muon_step_static")
 
 
 def muon_debug_read_update(ctx, index: int, dst_ptr: int, dst_dtype: int, stream_ptr: int = 0) -> None:

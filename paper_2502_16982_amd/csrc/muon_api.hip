@@ -44,6 +44,13 @@ int guarded(F&& body) noexcept {
   }
 }
 
+// Scratch of muon_step_static, the entry point for callers that cannot allocate device memory: the tables and
+// Newton-Schulz temporaries that muon_step keeps in the caller's workspace live in this array instead.  Every device
+// the library runs on holds its own copy, at its own address, until the process ends.  In host code the name is only
+// a handle for hipGetSymbolAddress; the device address it yields (StaticSlot::ptr) is what kernels and copies get.
+constexpr size_t kStaticScratchBytes = MUON_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 }  // namespace
 
 struct muon_ctx {
@@ -335,6 +342,106 @@ int muon_step(muon_ctx* ctx, const muon_param* params, int32_t n, const muon_hpa
   return guarded([&]() { return step_impl(ctx, params, n, hp, hip_stream, update_rms_out); });
 }
 
+}  // extern "C"
+
+namespace {
+
+constexpr int kStaticMaxDevices = 64;
+struct PtrPack {                     // the per-step pointers of muon_step_static travel as a kernel argument
+  MatPtrs p[MUON_STATIC_MAX_MATRICES];
+};
+struct StaticSlot {
+  unsigned char* ptr = nullptr;      // device address of `scratch` on this device (hipGetSymbolAddress)
+  muon_ctx* ctx = nullptr;           // plan and tables of the shape list of the last call on this device
+  std::vector<muon_param> key;       // that shape list (rows, cols, dtypes)
+};
+StaticSlot g_static[kStaticMaxDevices];
+
+__global__ void set_ptrs_kernel(PtrPack pack, MatPtrs* __restrict__ dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = pack.p[i];
+}
+
+int step_static_impl(const muon_param* params, int32_t n, int32_t ns_dtype, const muon_hparams* hp, void* hip_stream,
+                     float* update_rms_out) {
+  int st = validate_shapes(params, n, ns_dtype);
+  if (st != MUON_OK) return st;
+  if (!hp) return MUON_E_INVALID_ARG;
+  if (n > MUON_STATIC_MAX_MATRICES) return MUON_E_STATIC_LIMIT;
+  size_t need = 0;
+  st = plan_workspace_bytes(params, n, ns_dtype, 0, &need);
+  if (st != MUON_OK) return st;
+  if (need > kStaticScratchBytes) return MUON_E_STATIC_LIMIT;
+
+  int dev = 0;
+  MUON_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kStaticMaxDevices) return MUON_E_INVALID_ARG;
+  StaticSlot& slot = g_static[dev];
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (!slot.ptr) {                   // first call on this device: where does this device keep the array?
+    void* p = nullptr;
+    MUON_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return MUON_E_MISALIGNED;
+    MUON_HIP(gemm_setup());
+    slot.ptr = static_cast<unsigned char*>(p);
+  }
+  bool same = slot.ctx && slot.ctx->ns_dtype == ns_dtype && (int)slot.key.size() == n;
+  for (int i = 0; same && i < n; ++i)
+    same = slot.key[i].rows == params[i].rows && slot.key[i].cols == params[i].cols &&
+           slot.key[i].w_dtype == params[i].w_dtype && slot.key[i].g_dtype == params[i].g_dtype;
+  if (!same) {
+    // Another shape list than the last call's: plan again (host memory only) and put the new tables at the head of
+    // the scratch.  Earlier work on this stream may still be using the old tables, and the copy reads host memory
+    // that must outlive it: wait on both sides of it.  The array keeps whatever the last call left; nothing in it has
+    // to start at zero (every temporary is written in full before it is read), only the tables must be the new ones.
+    MUON_HIP(hipStreamSynchronize(s));
+    if (slot.ctx) {
+      muon_destroy(slot.ctx);
+      slot.ctx = nullptr;
+    }
+    muon_ctx* ctx = new muon_ctx();
+    struct Guard {
+      muon_ctx* c;
+      ~Guard() { if (c) muon_destroy(c); }
+    } guard{ctx};
+    ctx->n = n;
+    ctx->ns_dtype = ns_dtype;
+    ctx->device = dev;
+    ctx->ws = slot.ptr;
+    ctx->ws_bytes = kStaticScratchBytes;
+    st = plan_build(ctx->plan, params, n, ns_dtype, reinterpret_cast<uintptr_t>(slot.ptr), kStaticScratchBytes);
+    if (st != MUON_OK) return st;
+    if (ctx->plan.chunks.size() != 1) return MUON_E_STATIC_LIMIT;
+    ctx->d_mats = reinterpret_cast<MatDesc*>(ctx->ws + ctx->plan.off_mats);
+    ctx->d_ptrs = reinterpret_cast<MatPtrs*>(ctx->ws + ctx->plan.off_ptrs);
+    ctx->last_ptrs.resize(n);
+    MUON_HIP(hipMemcpyAsync(slot.ptr, ctx->plan.image.data(), ctx->plan.image.size(), hipMemcpyHostToDevice, s));
+    MUON_HIP(hipStreamSynchronize(s));
+    slot.key.assign(params, params + n);
+    slot.ctx = ctx;
+    guard.c = nullptr;
+  }
+  muon_ctx* ctx = slot.ctx;
+  ctx->ptrs_valid = true;            // check_step_args compares against last_ptrs only to report a change; unused here
+  bool changed = false;
+  st = check_step_args(ctx, params, n, hp, &changed);
+  if (st != MUON_OK) return st;
+  PtrPack pack{};
+  for (int i = 0; i < n; ++i) pack.p[i] = MatPtrs{params[i].w, params[i].g, params[i].m};
+  set_ptrs_kernel<<<1, MUON_STATIC_MAX_MATRICES, 0, s>>>(pack, ctx->d_ptrs, n);
+  MUON_HIP(hipGetLastError());
+  return enqueue_step(ctx, hp, s, update_rms_out);
+}
+
+}  // namespace
+
+extern "C" {
+
+int muon_step_static(const muon_param* params, int32_t n, int32_t ns_dtype, const muon_hparams* hp, void* hip_stream,
+                     float* update_rms_out) {
+  return guarded([&]() { return step_static_impl(params, n, ns_dtype, hp, hip_stream, update_rms_out); });
+}
+
 int muon_debug_read_update(muon_ctx* ctx, int32_t index, void* dst, int32_t dst_dtype, void* hip_stream) {
   if (!ctx || ctx->plan_only || !dst || index < 0 || index >= ctx->n) return MUON_E_INVALID_ARG;
   if (dst_dtype != MUON_F32 && dst_dtype != MUON_BF16) return MUON_E_UNSUPPORTED_DTYPE;
@@ -455,6 +562,7 @@ const char* muon_status_string(int status) {
     case MUON_E_NOT_RESIDENT: return "matrix temporaries are not resident";
     case MUON_E_MISALIGNED: return "misaligned buffer";
     case MUON_E_NO_MEMORY: return "out of host memory";
+    case MUON_E_STATIC_LIMIT: return "input exceeds the limits of muon_step_static";
     default: return "unknown status";
   }
 }

@@ -49,11 +49,11 @@ def test_default_hparams_are_the_papers(binding):
 def test_status_strings(binding):
     L = binding.lib()
     seen = set()
-    for code in range(0, -9, -1):
+    for code in range(0, -10, -1):
         s = L.muon_status_string(code).decode()
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert L.muon_status_string(-99).decode() == "unknown status"
 
 
