@@ -64,8 +64,9 @@ def calibrate_copy(mib=1024, repeats=5):
 
 def executed_ns_flops(wl, ns_steps, ns_dtype="bf16"):
     """Matrix-core flops actually issued, summed over the tile tables of the launch plan (host-only call into the
-    library): symmetric products compute only tiles on or above the diagonal; strip tiles that were shifted to end at
-    the matrix edge recompute what they overlap."""
+    library): symmetric products compute only tiles on or above the diagonal and, in plain bf16, only the upper triangle
+    of 32 x 32 blocks of a diagonal tile; strip tiles that were shifted to end at the matrix edge recompute what they
+    overlap."""
     from paper_2502_16982_amd import binding
     n = len(wl.shapes)
     p = binding.param_array(wl.shapes, [1] * n, [1] * n)
@@ -76,8 +77,8 @@ def executed_ns_flops(wl, ns_steps, ns_dtype="bf16"):
         flops = 0
         for product, k_of in (("gram", "n_pad"), ("poly", "m_pad"), ("apply", "m_pad")):
             for level in (0, 1):
-                for mat, _, _, rows, cols in binding.muon_plan_tiles(ctx, 0, product, level):
-                    flops += 2 * rows * cols * desc[mat][k_of]
+                for mat, _, _, _, _, blocks in binding.muon_plan_tiles(ctx, 0, product, level):
+                    flops += 2 * blocks * 1024 * desc[mat][k_of]
     finally:
         binding.muon_destroy(ctx)
     return ns_steps * flops

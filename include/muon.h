@@ -178,9 +178,11 @@ int muon_plan_only(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t 
  * (A = X X^T), 1 polynomial, 2 apply, 3 apply of the last iteration; `level`: 1 = the coarse launch of the
  * matrix-core paths (256 x 256 tiles, plus 512 x 128 tiles over the 128-wide column strip that an m_pad which is an
  * odd multiple of 128 leaves), 0 = the fine launch that takes the rest (128 x 128 tiles on the matrix-core paths,
- * 64 x 64 on the fp32 path, which has no coarse launch).  Writes up to `cap_records` records of five int32
- * {matrix index in the list, first row, first column, rows, columns} (in elements), in launch order, and returns the
- * number of records of the table (which may exceed cap_records) or a negative status.  Gram and polynomial tables
+ * 64 x 64 on the fp32 path, which has no coarse launch).  Writes up to `cap_records` records of six int32
+ * {matrix index in the list, first row, first column, rows, columns (in elements), number of 32 x 32 blocks of the
+ * tile that are computed}, in launch order, and returns the number of records of the table (which may exceed
+ * cap_records) or a negative status.  The block count is rows * columns / 1024 except for the 256 x 256 tiles on the
+ * diagonal of a symmetric product in plain bf16, which are computed from the 36 blocks of their upper triangle.  Gram and polynomial tables
  * hold tiles on and above the diagonal of the m_pad x m_pad output; apply tables hold the tiles of X'^T
  * (n_pad x m_pad) on the matrix-core paths and of X' (m_pad x n_pad) on the fp32 path.  The last 512 x 128 tile of
  * a strip is shifted to end at the matrix edge and may overlap its neighbour (both then write the same values).

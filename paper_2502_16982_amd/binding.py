@@ -238,15 +238,15 @@ PLAN_PRODUCTS = {"gram": 0, "poly": 1, "apply": 2, "apply_last": 3}
 
 
 def muon_plan_tiles(ctx, chunk: int, product: str, level: int) -> list:
-    """Tile table of one grouped launch of a host-only plan: [(matrix, row0, col0, rows, cols), ...] in elements."""
+    """Tile table of one grouped launch of a host-only plan: [(matrix, row0, col0, rows, cols, computed_blocks), ...]; offsets and extents in elements, blocks of 32 x 32."""
     count = lib().muon_plan_tiles(ctx, chunk, PLAN_PRODUCTS[product], level, None, 0)
     if count < 0:
         raise MuonError(count, "muon_plan_tiles")
-    buf = (C.c_int32 * (5 * max(count, 1)))()
+    buf = (C.c_int32 * (6 * max(count, 1)))()
     got = lib().muon_plan_tiles(ctx, chunk, PLAN_PRODUCTS[product], level, buf, count)
     if got != count:
         raise MuonError(got if got < 0 else -1, "muon_plan_tiles")
-    return [tuple(buf[5 * i:5 * i + 5]) for i in range(count)]
+    return [tuple(buf[6 * i:6 * i + 6]) for i in range(count)]
 
 
 def muon_profile_enable(ctx, enable: bool) -> None:

@@ -80,6 +80,15 @@ struct TileCfg {
   static constexpr size_t lds_bytes(int nstage) { return lds_main(nstage); }
 };
 
+// f(integral_constant<int, I>) for I = FIRST .. LAST-1, unrolled at compile time
+template <int FIRST, int LAST, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (FIRST < LAST) {
+    f(std::integral_constant<int, FIRST>{});
+    static_for<FIRST + 1, LAST>(f);
+  }
+}
+
 // s_waitcnt lgkmcnt(0), vmcnt untouched: this wave's LDS reads have returned
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (0 << 8)); }
 
@@ -145,7 +154,12 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
   static_assert(4 * FM == WTM / 8 && (WTM / 8 & (WTM / 8 - 1)) == 0 && BM / 8 >= 16, "slot addressing: 4i+q and wm*WTM/8 use disjoint bits");
   (void)NT;
 
-  const int tid = threadIdx.x, lane = tid & 63;
+  // The thread index is made opaque once per tile: everything below that derives from it (lane addresses, swizzle
+  // keys) is then recomputed for every tile of a persistent block instead of being hoisted out of the tile loop, where
+  // it would occupy registers for the whole kernel and push the epilogues into scratch.
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN_, wn = wave % WN_;
   const int row0 = tile.r0 * kTileUnit, col0 = tile.c0 * kTileUnit;
@@ -196,14 +210,7 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
                                          (lptr)(base + BM * ROWB + (n - LI) * NW * 1024), 16, 0, 0);
     }
   };
-  // A slab's requests: HEAD of them in phase C, TAIL in each of the next iteration's phases A and B.  Measured:
-  // moving requests into A and B (already dense with fragment reads) costs more there than it saves in C.
-  constexpr int TAIL = 0, HEAD = NLOAD - 2 * TAIL;
   using Zero = std::integral_constant<int, 0>;
-  using HeadN = std::integral_constant<int, HEAD>;
-  using TailA0 = std::integral_constant<int, HEAD>;
-  using TailB0 = std::integral_constant<int, HEAD + TAIL>;
-  using TailN = std::integral_constant<int, TAIL>;
   using AllN = std::integral_constant<int, NLOAD>;
 
   // ---- fragment addressing: lane (r = lane%32, h = lane/32) reads logical chunk 2*kk + h of its row ----
@@ -292,19 +299,24 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
     }
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
   };
-  // ---- pipeline: two LDS stages.  A wave instruction that requests 1 KB keeps the wave's (in-order) issue port
-  // busy until the memory pipeline accepts it - measured ~57 clocks each when 4 waves request 16 KB apiece in a
-  // burst - so requests are never issued in a burst: one request follows every second MFMA of phase C.  The
-  // loop is skewed by one k-step so that no MFMA ever waits for LDS latency.  Iteration kt (slab kt sits in
-  // stage `cur`, the other stage is `cur^1`):
-  //   A  MFMAs of k-step 3 of slab kt-1 | fragment reads of k-steps 0, 1 of slab kt
+  // ---- pipeline: two LDS stages.  Measured on this chip: a wave instruction that requests 1 KB keeps the wave's
+  // (in-order) issue port busy until the memory pipeline accepts it (~57 clocks each when 4 waves request 16 KB
+  // apiece in a burst), and the 4 waves' fragment reads fill the LDS port completely when all of a slab's reads sit
+  // in half an iteration.  So requests are never issued in a burst (one after every second MFMA of phase C), and the
+  // fragment reads of a slab are spread over three phases: the k-step-0 fragments of the NEXT slab are read during
+  // phase C (moving them there from phase A took 8-10 % off the main loop).  That needs slab kt+1 in LDS when phase
+  // C of iteration kt starts, so one barrier per iteration does both jobs: "stage cur may be overwritten" and "slab
+  // kt+1 is visible".  The loop is skewed by one k-step so that no MFMA waits for LDS latency.  Iteration kt (slab kt
+  // sits in stage `cur`, slab kt+1 in `cur^1`; the k-step-0 fragments of slab kt are already in registers):
+  //   A  MFMAs of k-step 3 of slab kt-1 | fragment reads of k-step 1
   //   B  MFMAs of k-step 0              | fragment reads of k-steps 2, 3
-  //      barrier #1: nobody reads stage `cur` any more
+  //      wait: my reads of stage `cur` and my requests of slab kt+1 have completed; barrier
   //   C  MFMAs of k-steps 1, 2          | the requests of slab kt+2, into stage `cur`
-  //      wait until slab kt+1 (requested one iteration ago) has landed, barrier #2.
+  //                                     | fragment reads of k-step 0 of slab kt+1
   const int KT = NSEG * KT1;
   request_part(0, 0, Zero{}, AllN{});
-  if (KT > 1) { request_part(1, 1, Zero{}, HeadN{}); wait_vmcnt<HEAD>(); } else { wait_vmcnt<0>(); }
+  if (KT > 1) request_part(1, 1, Zero{}, AllN{});
+  wait_vmcnt<0>();
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -318,6 +330,13 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
   for (int j = 0; j < FN; ++j)
 #pragma unroll
     for (int t = 0; t < 8; ++t) bfr[KSTEPS - 1][j][t] = (__bf16)0.0f;
+  // k-step 0 of slab 0 (on the K-major path the first iteration's waits cover these reads like any others)
+  if (LKM) {
+#pragma unroll
+    for (int r = 0; r < RPS; ++r) read_one(0, 0, r);
+  } else {
+    fread(0, 0);
+  }
 
   // Transposed addend tile -> LDS image [BN][BM]; wave-level DMA instruction idx fills image bytes [1024 idx, +1024).
   // The half of the image that lies in the stage the last iteration no longer needs is requested during that
@@ -329,44 +348,56 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
   static_assert(CPT <= 64, "one wave instruction covers at least one row of the transposed image");
   constexpr int TI = BN / RPI_T / NW;            // DMA instructions (or 64-lane store groups) per wave
   constexpr int IPS = STAGE_B / 1024 / NW;       // image DMA instructions per wave that land in one pipeline stage
-  auto et_request = [&](int region, int plane = 0) {   // requests the part of the image that overlays pipeline stage `region`
-    if (region * IPS >= TI) return;
+  constexpr int CNT0 = IPS < TI ? IPS : TI, CNT1 = TI - CNT0 < IPS ? TI - CNT0 : IPS;   // instructions per region
+  // instruction i of the part of the image that overlays pipeline stage `region` (the last region may hold fewer
+  // instructions than a stage has room for)
+  auto et_request_one = [&](int region, int i, int plane = 0) {
+    if (i >= (region == 0 ? CNT0 : CNT1)) return;
     const int idx0 = region * IPS * NW + wave;
-    const int c0 = idx0 * RPI_T + lane / CPT;
-    const u16* src = Et + (size_t)(col0 + c0) * p.ldet + row0;
+    const int c = idx0 * RPI_T + lane / CPT + i * NW * RPI_T;
+    const u16* src = Et + (size_t)(col0 + c) * p.ldet + row0;
     if constexpr (PL > 1) src += (size_t)plane * (size_t)p.et_plane;
-    unsigned char* dstl = smem + idx0 * 1024;
+    const int chunk = (lane % CPT) ^ (c & KEYMASK);
+    __builtin_amdgcn_global_load_lds((gptr)(src + chunk * 8), (lptr)(smem + idx0 * 1024 + i * NW * 1024), 16, 0, 0);
+  };
+  auto et_request = [&](int region, int plane = 0) {
 #pragma unroll
-    for (int i = 0; i < (IPS < TI ? IPS : TI); ++i) {
-      if (region * IPS + i >= TI) break;         // the last region may hold fewer instructions than a stage has room for
-      const int c = c0 + i * NW * RPI_T;
-      const int chunk = (lane % CPT) ^ (c & KEYMASK);
-      __builtin_amdgcn_global_load_lds((gptr)(src + (size_t)(i * NW * RPI_T) * p.ldet + chunk * 8), (lptr)(dstl + i * NW * 1024), 16, 0, 0);
-    }
+    for (int i = 0; i < CNT0; ++i) et_request_one(region, i, plane);
   };
 
   int cur = 0;
   int kt = 0;
-  // one iteration; REFILL: slab kt+2 exists; SYNC: slab kt+1 exists (its last requests are issued here and it
-  // must be visible afterwards)
+  // one iteration; REFILL: slab kt+2 exists (requested here); SYNC: slab kt+1 exists (its k-step-0 fragments are
+  // read here).  Every MFMA of phases A and C is followed by its share of the phase's other instructions and a
+  // scheduling fence, so the instruction order is the one written here.
+  constexpr int MT = FM * FN;                    // MFMAs per k-step
+  constexpr int NR = LKM ? RPS : FM + FN;        // LDS read instructions per k-step
+  auto read_frag = [&](int stage, int kk, int r) {
+    if (LKM) {
+      read_one(stage, kk, r);
+    } else {
+      const unsigned char* sp = smem + stage * STAGE_B + (((2 * kk + fh) ^ fkey) * 16);
+      if (r < FM) af[kk][r] = *reinterpret_cast<const bf16x8*>(sp + a_base + r * 32 * ROWB);
+      else bfr[kk][r - FM] = *reinterpret_cast<const bf16x8*>(sp + b_base + (r - FM) * 32 * ROWB);
+    }
+  };
   auto iteration = [&](auto refill_tag, auto sync_tag) {
     constexpr bool REFILL = decltype(refill_tag)::value, SYNC = decltype(sync_tag)::value;
-    constexpr int DSG = 2 * ((LKM ? 2 : 1) * FM + FN) / (FM + FN);   // LDS reads per scheduling group of phases A, B
+    // A: reads of k-step 1 under the MFMAs of k-step 3 of the previous slab
+    static_for<0, MT>([&](auto t_tag) {
+      constexpr int t = decltype(t_tag)::value;
+      mma_one(KSTEPS - 1, t);
+#pragma unroll
+      for (int r = t * NR / MT; r < (t + 1) * NR / MT; ++r) read_frag(cur, 1, r);
+      __builtin_amdgcn_sched_barrier(0);
+    });
     if (LKM) {
-      constexpr int NG = FM + FN, RG = 2 * RPS / NG, MT = FM * FN;
+      constexpr int NG = FM + FN, RG = 2 * RPS / NG;
       constexpr int LEAD = MT >= NG + 2 ? 2 : 0; // MFMAs of k-step 0 issued ahead of phase B's reads
-      static_assert(!LKM || (2 * RPS % NG == 0 && MT % NG == 0 && MT >= NG + LEAD), "K-major phase layout");
-      // A: reads of k-steps 0, 1 under the MFMAs of k-step 3 of the previous slab
-#pragma unroll
-      for (int g = 0; g < NG; ++g) {
-#pragma unroll
-        for (int r = 0; r < RG; ++r) read_one(cur, (g * RG + r) / RPS, (g * RG + r) % RPS);
-#pragma unroll
-        for (int t = 0; t < MT / NG; ++t) mma_one(KSTEPS - 1, g * (MT / NG) + t);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // B: MFMAs of k-step 0 lead, then one per group of reads of k-steps 2, 3
-      land_kstep(0, std::integral_constant<int, (RPS < 15 ? RPS : 15)>{}, true);   // lgkmcnt(RPS): k-step 0 is in
+      static_assert(!LKM || (2 * RPS % NG == 0 && MT >= NG + LEAD), "K-major phase layout");
+      // B: MFMAs of k-step 0 lead, then one per group of reads of k-steps 2, 3.  The k-step-0 fragments were read
+      // during the previous phase C; the reads of k-step 1 (RPS of them) may still be in flight.
+      land_kstep(0, std::integral_constant<int, (RPS < 15 ? RPS : 15)>{}, true);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < LEAD; ++t) mma_one(0, t);
@@ -386,69 +417,49 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
       land_kstep(3, Zero{}, false);
       __builtin_amdgcn_sched_barrier(0);
     } else {
-    // A
-    fread(cur, 0);
-    fread(cur, 1);
-    if (SYNC && TAIL > 0) request_part(kt + 1, cur ^ 1, TailA0{}, TailN{});
-    mma(KSTEPS - 1);
+      // B.  MFMAs go first: the LDS counter is only 4 bits wide, so a wait placed behind more than 15 younger reads
+      // degenerates into "wait for everything".
+      constexpr int DSG = 2;                     // LDS reads per scheduling group
+      fread(cur, 2);
+      fread(cur, 3);
+      mma(0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
 #pragma unroll
-    for (int g = 0; g < FM + FN; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x100, DSG, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, (FM * FN) / (FM + FN), 0);
-      if (SYNC && TAIL > 0 && g % ((FM + FN) / (TAIL > 0 ? TAIL : 1)) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // B.  MFMAs go first: the LDS counter is only 4 bits wide, so a wait placed behind more than 15 younger reads
-    // degenerates into "wait for everything".
-    fread(cur, 2);
-    fread(cur, 3);
-    if (SYNC && TAIL > 0) request_part(kt + 1, cur ^ 1, TailB0{}, TailN{});
-    mma(0);
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-#pragma unroll
-    for (int g = 0; g < FM + FN; ++g) {
-      __builtin_amdgcn_sched_group_barrier(0x100, DSG, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (SYNC && TAIL > 0 && g % ((FM + FN) / (TAIL > 0 ? TAIL : 1)) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    }
-    if (REFILL) {
-      wait_lgkm0();                              // my fragment reads have returned
-      __builtin_amdgcn_s_barrier();              // barrier #1: stage `cur` is free
-      request_part(kt + 2, cur, Zero{}, HeadN{});
-    }
-    // C
-    if (PL == 1 && !REFILL && !SYNC && Et) et_request(cur ^ 1);
-#pragma unroll
-    for (int kk = 1; kk < KSTEPS - 1; ++kk) {
-      if (LKM) {
-#pragma unroll
-        for (int t = 0; t < FM * FN; ++t) mma_one(kk, t);
-      } else {
-        mma(kk);
+      for (int g = 0; g < FM + FN; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x100, DSG, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (!REFILL && !SYNC) {
-#pragma unroll
-      for (int g = 0; g < 8; ++g) {
-        __builtin_amdgcn_sched_group_barrier(0x008, ((KSTEPS - 2) * FM * FN) / 8, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
-      }
-    }
-    if (REFILL) {
-#pragma unroll
-      for (int g = 0; g < HEAD; ++g) {
-        __builtin_amdgcn_sched_group_barrier(0x008, ((KSTEPS - 2) * FM * FN) / HEAD, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
     if (SYNC) {
-      if (REFILL) wait_vmcnt<HEAD>(); else wait_vmcnt<0>();   // slab kt+1 has landed (the head of slab kt+2 may be in flight)
-      __builtin_amdgcn_s_barrier();              // barrier #2: ... for every wave
+      wait_lgkm0();                              // my fragment reads of stage `cur` have returned
+      wait_vmcnt<0>();                           // my requests of slab kt+1 have landed
+      __builtin_amdgcn_s_barrier();              // ... everybody's: stage `cur` is free and slab kt+1 is visible
     }
+    // C: 2 MT MFMAs; among them, evenly, the NLOAD requests of slab kt+2, the NR reads of k-step 0 of slab kt+1 and, in
+    // the last iteration, the part of the addend image that overlays the stage no longer in use
+    constexpr int NC = (KSTEPS - 2) * MT;
+    constexpr bool EARLY_ET = PL == 1 && !REFILL && !SYNC;
+    const bool early_et = EARLY_ET && Et != nullptr;
+    static_for<0, NC>([&](auto t_tag) {
+      constexpr int t = decltype(t_tag)::value;
+      mma_one(1 + t / MT, t % MT);
+      if constexpr (REFILL) {
+        static_for<t * NLOAD / NC, (t + 1) * NLOAD / NC>([&](auto n_tag) { request_part(kt + 2, cur, n_tag, std::integral_constant<int, 1>{}); });
+      }
+      if constexpr (SYNC) {
+#pragma unroll
+        for (int r = t * NR / NC; r < (t + 1) * NR / NC; ++r) read_frag(cur ^ 1, 0, r);
+      }
+      if constexpr (EARLY_ET) {
+        if (early_et) {
+#pragma unroll
+          for (int i = t * CNT0 / NC; i < (t + 1) * CNT0 / NC; ++i) et_request_one(cur ^ 1, i);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
     cur ^= 1;
     ++kt;
   };
@@ -809,6 +820,274 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Diagonal 256 x 256 tiles of the symmetric products (L = R, plain bf16).  Such a tile is symmetric itself: of its
+// 8 x 8 blocks of 32 x 32 only the 36 on or above the diagonal are computed, dealt 9 to a wave (against 16 a wave in
+// an ordinary tile), and both the block and - for the 28 off the diagonal - its transpose are written into ONE image of
+// the tile.  The tile needs one operand panel instead of two, so a pipeline stage is 32 KB and a slab takes 8 requests
+// per wave.  Everything else (slab pipeline, swizzles, image store) is the ordinary tile's.
+//
+// A wave's share: the blocks (bi[t], bj[t]), bi <= bj, and the set fb[] of 32-row panel blocks their operands come from
+// (fa[t] / fc[t]: positions of bi[t] / bj[t] in fb).
+struct DiagWave0 {   // rows 0-2 x columns 3-5
+  static constexpr int N = 9, NF = 6;
+  static constexpr int bi[N] = {0, 0, 0, 1, 1, 1, 2, 2, 2}, bj[N] = {3, 4, 5, 3, 4, 5, 3, 4, 5};
+  static constexpr int fb[NF] = {0, 1, 2, 3, 4, 5};
+  static constexpr int fa[N] = {0, 0, 0, 1, 1, 1, 2, 2, 2}, fc[N] = {3, 4, 5, 3, 4, 5, 3, 4, 5};
+};
+struct DiagWave1 {   // triangle of rows 0-2, and rows 3-5 x column 6
+  static constexpr int N = 9, NF = 7;
+  static constexpr int bi[N] = {0, 0, 0, 1, 1, 2, 3, 4, 5}, bj[N] = {0, 1, 2, 1, 2, 2, 6, 6, 6};
+  static constexpr int fb[NF] = {0, 1, 2, 3, 4, 5, 6};
+  static constexpr int fa[N] = {0, 0, 0, 1, 1, 2, 3, 4, 5}, fc[N] = {0, 1, 2, 1, 2, 2, 6, 6, 6};
+};
+struct DiagWave2 {   // triangle of rows 3-5, and rows 3-5 x column 7
+  static constexpr int N = 9, NF = 4;
+  static constexpr int bi[N] = {3, 3, 3, 4, 4, 5, 3, 4, 5}, bj[N] = {3, 4, 5, 4, 5, 5, 7, 7, 7};
+  static constexpr int fb[NF] = {3, 4, 5, 7};
+  static constexpr int fa[N] = {0, 0, 0, 1, 1, 2, 0, 1, 2}, fc[N] = {0, 1, 2, 1, 2, 2, 3, 3, 3};
+};
+struct DiagWave3 {   // rows 0-2 x columns 6-7, and the triangle of rows 6-7
+  static constexpr int N = 9, NF = 5;
+  static constexpr int bi[N] = {0, 0, 1, 1, 2, 2, 6, 6, 7}, bj[N] = {6, 7, 6, 7, 6, 7, 6, 7, 7};
+  static constexpr int fb[NF] = {0, 1, 2, 6, 7};
+  static constexpr int fa[N] = {0, 0, 1, 1, 2, 2, 3, 3, 4}, fc[N] = {3, 4, 3, 4, 3, 4, 3, 4, 4};
+};
+
+template <typename W>
+__device__ __forceinline__ void diag_wave_body(const GemmProblem& p, int row0, unsigned char* smem, float beta_acc, float beta_e,
+                                               int alpha_idx, float diag_add, int tid) {
+  constexpr int BM = 256, NW = 4, N = W::N, NF = W::NF;
+  constexpr int LI = BM / 8 / NW;                  // DMA instructions per wave per slab
+  constexpr int STAGE_B = BM * ROWB;               // one operand panel per stage
+  constexpr int KSTEPS = BK / 16;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // requests: as in the ordinary tile (8 rows x 128 B per wave instruction, chunks XOR-swizzled by (row/2)%8)
+  const int dma_row = wave * 8 + (lane >> 3);
+  const int dma_chunk = (lane & 7) ^ (((lane >> 4) & 3) + 4 * (wave & 1));
+  const u16* lsrc = static_cast<const u16*>(p.L) + (size_t)(row0 + dma_row) * p.ldl + dma_chunk * 8;
+  const size_t lstep = (size_t)(8 * NW) * p.ldl;
+  auto request_one = [&](int kt, int stage, int n) {
+    __builtin_amdgcn_global_load_lds((gptr)(lsrc + n * lstep + (size_t)kt * BK),
+                                     (lptr)(smem + stage * STAGE_B + wave * 1024 + n * NW * 1024), 16, 0, 0);
+  };
+  const int fr = lane & 31, fh = lane >> 5;
+  const int fkey = (fr >> 1) & 7;
+  f32x16 acc[N];
+#pragma unroll
+  for (int t = 0; t < N; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  bf16x8 fg[KSTEPS][NF];
+  auto read_frag = [&](int stage, int kk, int f) {
+    fg[kk][f] = *reinterpret_cast<const bf16x8*>(smem + stage * STAGE_B + (32 * W::fb[f] + fr) * ROWB + (((2 * kk + fh) ^ fkey) * 16));
+  };
+  auto mma_one = [&](int kk, int t) {
+    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg[kk][W::fa[t]], fg[kk][W::fc[t]], acc[t], 0, 0, 0);
+  };
+
+  // addend image [256][256] (transposed addend = the addend itself, the matrix being symmetric): instruction i of the
+  // image half `half` (64 KB each; the upper half lies beyond both pipeline stages and can be requested at any time)
+  const u16* Et = static_cast<const u16*>(p.Et);
+  constexpr int CPT = BM / 8, KEYMASK = 31, RPI_T = 2, TI = BM / RPI_T / NW;   // 32 chunks per image row, 32 instr per wave
+  auto et_request_one = [&](int half, int i) {
+    const int idx0 = half * (TI / 2) * NW + wave;
+    const int c = idx0 * RPI_T + lane / CPT + i * NW * RPI_T;
+    const int chunk = (lane % CPT) ^ (c & KEYMASK);
+    __builtin_amdgcn_global_load_lds((gptr)(Et + (size_t)(row0 + c) * p.ldet + row0 + chunk * 8),
+                                     (lptr)(smem + idx0 * 1024 + i * NW * 1024), 16, 0, 0);
+  };
+
+  // ---- main loop: the ordinary tile's pipeline (see there) with 9 MFMAs per k-step ----
+  const int KT = p.K / BK;
+#pragma unroll
+  for (int n = 0; n < LI; ++n) request_one(0, 0, n);
+  if (KT > 1) {
+#pragma unroll
+    for (int n = 0; n < LI; ++n) request_one(1, 1, n);
+  }
+  wait_vmcnt<0>();
+  __syncthreads();
+#pragma unroll
+  for (int f = 0; f < NF; ++f)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) fg[KSTEPS - 1][f][t] = (__bf16)0.0f;     // first pass of phase A multiplies zeros
+#pragma unroll
+  for (int f = 0; f < NF; ++f) read_frag(0, 0, f);
+  int cur = 0, kt = 0;
+  auto iteration = [&](auto refill_tag, auto sync_tag) {
+    constexpr bool REFILL = decltype(refill_tag)::value, SYNC = decltype(sync_tag)::value;
+    // A: MFMAs of k-step 3 of the previous slab | reads of k-step 1
+    static_for<0, N>([&](auto t_tag) {
+      constexpr int t = decltype(t_tag)::value;
+      mma_one(KSTEPS - 1, t);
+#pragma unroll
+      for (int f = t * NF / N; f < (t + 1) * NF / N; ++f) read_frag(cur, 1, f);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // B: MFMAs of k-step 0 | reads of k-steps 2, 3
+    static_for<0, N>([&](auto t_tag) {
+      constexpr int t = decltype(t_tag)::value;
+      mma_one(0, t);
+#pragma unroll
+      for (int r = t * 2 * NF / N; r < (t + 1) * 2 * NF / N; ++r) read_frag(cur, 2 + r / NF, r % NF);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if (SYNC) {
+      wait_lgkm0();                              // my fragment reads of stage `cur` have returned
+      wait_vmcnt<0>();                           // my requests of slab kt+1 have landed
+      __builtin_amdgcn_s_barrier();              // ... everybody's: stage `cur` is free and slab kt+1 is visible
+    }
+    // C: MFMAs of k-steps 1, 2 | requests of slab kt+2 | reads of k-step 0 of slab kt+1 | in the last iteration the
+    // upper half of the addend image
+    constexpr int NC = 2 * N;
+    const bool early_et = !REFILL && !SYNC && Et != nullptr;
+    static_for<0, NC>([&](auto t_tag) {
+      constexpr int t = decltype(t_tag)::value;
+      mma_one(1 + t / N, t % N);
+      if constexpr (REFILL) {
+#pragma unroll
+        for (int n = t * LI / NC; n < (t + 1) * LI / NC; ++n) request_one(kt + 2, cur, n);
+      }
+      if constexpr (SYNC) {
+#pragma unroll
+        for (int f = t * NF / NC; f < (t + 1) * NF / NC; ++f) read_frag(cur ^ 1, 0, f);
+      }
+      if constexpr (!REFILL && !SYNC) {
+        if (early_et) {
+#pragma unroll
+          for (int i = t * (TI / 2) / NC; i < (t + 1) * (TI / 2) / NC; ++i) et_request_one(1, i);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    cur ^= 1;
+    ++kt;
+  };
+  using T_ = std::true_type;
+  using F_ = std::false_type;
+  while (kt + 2 < KT) iteration(T_{}, T_{});
+  if (kt + 1 < KT) iteration(F_{}, T_{});
+  iteration(F_{}, F_{});
+#pragma unroll
+  for (int t = 0; t < N; ++t) mma_one(KSTEPS - 1, t);
+
+  // ---- epilogue: val = alpha * (beta_acc * acc + beta_e * E) (+ the diagonal constant), one rounding to bf16 ----
+  wait_vmcnt<0>();
+  __syncthreads();                               // every wave is done with the pipeline stages
+  const float alpha = alpha_idx >= 0 ? p.scal[alpha_idx] : 1.f;
+  const float ab_acc = alpha * beta_acc, ab_e = alpha * beta_e;
+  if (Et) {
+#pragma unroll
+    for (int i = 0; i < TI / 2; ++i) et_request_one(0, i);
+    wait_vmcnt<0>();
+    __syncthreads();
+  }
+  // Block (bi, bj) as the accumulators hold it: lane (fr, fh) owns column fr of block column bj and rows 8q + 4fh + e
+  // of block row bi, i.e. 8 contiguous bytes of image row 32 bj + fr (16-byte chunk 4 bi + q, half fh; the chunk position is
+  // XOR-swizzled by the image row's low 5 bits = fr): the image then holds the block transposed, which by symmetry
+  // is the tile's block (bj, bi).  For bi < bj the block itself is produced by a transpose on the matrix cores and
+  // written to image rows 32 bi + fr, chunks 4 bj + q - slots of a block below the diagonal, which nobody computes.
+  auto slot = [&](int brow, int bchunk, int q) -> unsigned char* {
+    return smem + (32 * brow + fr) * (BM * 2) + ((((4 * bchunk + q) ^ fr) & (CPT - 1)) << 4) + fh * 8;
+  };
+  bf16x8 sel[2];                                 // 0/1 selector of the MFMA transpose (see the ordinary tile)
+#pragma unroll
+  for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int row = 16 * sx + 4 * fh + (t < 4 ? t : 4 + t);
+      sel[sx][t] = (__bf16)(fr == row ? 1.0f : 0.0f);
+    }
+  const bool add_diag = p.diag_add != 0;
+#pragma unroll
+  for (int t = 0; t < N; ++t) {
+    u32x2 pk[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float x[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = ab_acc * acc[t][4 * q + e];
+      if (Et) {
+        const u32x2 e2 = *reinterpret_cast<const u32x2*>(slot(W::bj[t], W::bi[t], q));
+        x[0] = fmaf(ab_e, __uint_as_float(e2.x << 16), x[0]);
+        x[1] = fmaf(ab_e, __uint_as_float(e2.x & 0xffff0000u), x[1]);
+        x[2] = fmaf(ab_e, __uint_as_float(e2.y << 16), x[2]);
+        x[3] = fmaf(ab_e, __uint_as_float(e2.y & 0xffff0000u), x[3]);
+      }
+      if (W::bi[t] == W::bj[t] && add_diag) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] += (fr == 8 * q + 4 * fh + e) ? diag_add : 0.f;
+      }
+      const f32x2 lo = {x[0], x[1]}, hi = {x[2], x[3]};
+      pk[q].x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
+      pk[q].y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2));
+      *reinterpret_cast<u32x2*>(slot(W::bj[t], W::bi[t], q)) = pk[q];
+    }
+    if (W::bi[t] != W::bj[t]) {
+      f32x16 d;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) d[v] = 0.f;
+#pragma unroll
+      for (int sx = 0; sx < 2; ++sx) {
+        const u32x4 raw = {pk[2 * sx].x, pk[2 * sx].y, pk[2 * sx + 1].x, pk[2 * sx + 1].y};
+        d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), sel[sx], d, 0, 0, 0);
+      }
+      // this lane now holds row fr of the block, columns 8q + 4fh + e
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const f32x2 lo = {d[4 * q], d[4 * q + 1]}, hi = {d[4 * q + 2], d[4 * q + 3]};
+        u32x2 w;
+        w.x = __builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2));
+        w.y = __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2));
+        *reinterpret_cast<u32x2*>(slot(W::bi[t], W::bj[t], q)) = w;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __syncthreads();
+  // the image leaves with coalesced 16-byte stores (image row c = output row row0 + c)
+  {
+    u16* C = static_cast<u16*>(p.C);
+    constexpr int CSTEP = NW * RPI_T, PERIOD = (KEYMASK + 1) / CSTEP, SB = 8;
+    const int c_first = wave * RPI_T + lane / CPT;
+    u16* dst[PERIOD];
+#pragma unroll
+    for (int k = 0; k < PERIOD; ++k) {
+      const int c = c_first + k * CSTEP;
+      dst[k] = C + (size_t)(row0 + c) * p.ldc + row0 + ((lane % CPT) ^ (c & KEYMASK)) * 8;
+    }
+    const size_t dstep = (size_t)(CSTEP * PERIOD) * p.ldc;
+#pragma unroll
+    for (int i0 = 0; i0 < TI; i0 += SB) {
+      u32x4 v[SB];
+#pragma unroll
+      for (int u = 0; u < SB; ++u) v[u] = *reinterpret_cast<const u32x4*>(smem + ((i0 + u) * NW + wave) * 1024 + lane * 16);
+#pragma unroll
+      for (int u = 0; u < SB; ++u) {
+        const int i = i0 + u;
+        *(gvec_ptr)(dst[i % PERIOD] + (size_t)(i / PERIOD) * dstep) = v[u];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+__device__ __forceinline__ void diag_tile_body(const GemmProblem& p, const GemmTile& tile, unsigned char* smem, float beta_acc,
+                                               float beta_e, int alpha_idx, float diag_add) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));                  // see gemm_tile_body
+  const int row0 = tile.r0 * kTileUnit;
+  switch (__builtin_amdgcn_readfirstlane(tid >> 6)) {
+    case 0: diag_wave_body<DiagWave0>(p, row0, smem, beta_acc, beta_e, alpha_idx, diag_add, tid); break;
+    case 1: diag_wave_body<DiagWave1>(p, row0, smem, beta_acc, beta_e, alpha_idx, diag_add, tid); break;
+    case 2: diag_wave_body<DiagWave2>(p, row0, smem, beta_acc, beta_e, alpha_idx, diag_add, tid); break;
+    default: diag_wave_body<DiagWave3>(p, row0, smem, beta_acc, beta_e, alpha_idx, diag_add, tid); break;
+  }
+}
+
 // ---- kernels.  Fine launch: 128 x 128 tiles, two blocks per compute unit.  Coarse launch: one block per compute
 // unit, each block running the shape its table entry names - 256 x 256 (2 x 2 waves) or 512 x 128 (4 x 1 waves; the
 // 128-wide strips that an odd multiple of 128 leaves beside the 256-tiles).  Both coarse shapes give every wave a
@@ -829,18 +1108,32 @@ __global__ __launch_bounds__(256, 2) void ns_gemm_bf16_fine_kernel(const GemmPro
   gemm_tile_body<128, 128, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
 }
 
+// Block b works through table entries b, b + gridDim.x, ...  Launched with one block per tile, or persistent: one
+// block per compute unit (a multiple of the 8 dies, so an entry still runs on die index % 8); a persistent block that
+// goes on to its next tile neither waits for its stores to drain nor is re-dispatched, and its next tile's first
+// operand requests overlap both (measured +2 % on the MoE bank; with tiles of mixed K the static dealing loses that
+// again, so such launches stay one block per tile).
 template <bool LKM, int PL>
 __global__ __launch_bounds__(256, 1) void ns_gemm_bf16_kernel(const GemmProblem* __restrict__ probs,
-                                                               const GemmTile* __restrict__ tiles, float beta_acc,
+                                                               const GemmTile* __restrict__ tiles, int n_tiles, float beta_acc,
                                                                float beta_e, int alpha_idx, float diag_add) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const GemmTile tile = tiles[blockIdx.x];
-  const GemmProblem p = probs[tile.prob];
-  if (__builtin_amdgcn_readfirstlane(tile.shape) == kShape512x128)
-    gemm_tile_body<512, 128, 4, 1, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
-  else
-    gemm_tile_body<256, 256, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+  for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+    const GemmTile tile = tiles[t];
+    const GemmProblem p = probs[tile.prob];
+    const int shape = __builtin_amdgcn_readfirstlane(tile.shape);
+    if (shape == kShape512x128) {
+      gemm_tile_body<512, 128, 4, 1, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+    } else if (!LKM && PL == 1 && shape == kShape256Diag) {
+      if constexpr (!LKM && PL == 1) diag_tile_body(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+    } else {
+      gemm_tile_body<256, 256, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+    }
+    __syncthreads();        // every wave has read its part of the LDS images: the next tile may overwrite them
+  }
 }
+
+int g_coarse_grid = 0;      // blocks of a coarse launch: one per compute unit (set by gemm_setup)
 
 template <bool LKM, int PL>
 hipError_t setup_pair() {
@@ -852,18 +1145,25 @@ hipError_t setup_pair() {
 }
 
 template <bool LKM, int PL>
-void launch_one(int coarse, int strips, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
+void launch_one(int coarse, int flags, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
                 float beta_e, int alpha_idx, float diag_add, hipStream_t s) {
   if (!coarse)
     ns_gemm_bf16_fine_kernel<LKM, PL><<<n_tiles, 256, kLds128, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
   else
-    ns_gemm_bf16_kernel<LKM, PL><<<n_tiles, 256, strips ? kLds512 : kLds256, s>>>(probs, tiles, beta_acc, beta_e, alpha_idx, diag_add);
+    ns_gemm_bf16_kernel<LKM, PL><<<(flags & kGemmPersistent) && n_tiles > g_coarse_grid ? g_coarse_grid : n_tiles, 256,
+                                   (flags & kGemmStrips) ? kLds512 : kLds256, s>>>(
+        probs, tiles, n_tiles, beta_acc, beta_e, alpha_idx, diag_add);
 }
 
 }  // namespace
 
 hipError_t gemm_setup() {
-  hipError_t e = setup_pair<false, 1>();
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  g_coarse_grid = cus > 0 ? cus : 256;
+  e = setup_pair<false, 1>();
   if (e == hipSuccess) e = setup_pair<true, 1>();
   if (e == hipSuccess) e = setup_pair<false, 2>();
   if (e == hipSuccess) e = setup_pair<true, 2>();
@@ -872,12 +1172,12 @@ hipError_t gemm_setup() {
   return e;
 }
 
-hipError_t launch_gemm_bf16(int coarse, int strips, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
+hipError_t launch_gemm_bf16(int coarse, int flags, const GemmProblem* probs, const GemmTile* tiles, int n_tiles, float beta_acc,
                             float beta_e, int alpha_idx, float diag_add, int l_kmajor, int planes, hipStream_t s) {
   if (n_tiles <= 0) return hipSuccess;
   if (planes < 1 || planes > kMaxPlanes) return hipErrorInvalidValue;
 #define MUON_GEMM_CASE(K, P)                                                                                     \
-  if ((l_kmajor != 0) == K && planes == P) launch_one<K, P>(coarse, strips, probs, tiles, n_tiles, beta_acc, beta_e, alpha_idx, diag_add, s)
+  if ((l_kmajor != 0) == K && planes == P) launch_one<K, P>(coarse, flags, probs, tiles, n_tiles, beta_acc, beta_e, alpha_idx, diag_add, s)
   MUON_GEMM_CASE(false, 1);
   MUON_GEMM_CASE(true, 1);
   MUON_GEMM_CASE(false, 2);

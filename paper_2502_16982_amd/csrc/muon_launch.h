@@ -20,10 +20,13 @@ hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, 
 // a4-a6: grouped NT GEMM with fused epilogue.  alpha_idx: -1 none, 0 -> scal[0], 1 -> scal[1].  diag_add: constant
 // added to the diagonal of the outputs of problems that ask for it (GemmProblem::diag_add), bf16 kernel only.
 // coarse: 0 = every tile of the table is 128 x 128 (two blocks per compute unit); 1 = the table mixes 256 x 256 and,
-// when `strips` is set, 512 x 128 tiles (one block per compute unit; `strips` selects the larger LDS allocation).
+// with kGemmStrips in `flags`, 512 x 128 tiles (one block per compute unit; the flag selects the larger LDS
+// allocation).  kGemmPersistent: one block per compute unit works through the table with stride gridDim (for launches
+// whose tiles all cost the same; with mixed K the hardware's dynamic block dispatch balances better).
 // l_kmajor: every problem of the launch stores its L operand K-major (element (i, k) at L[k * ldl + i]).
 // planes: 1 = plain bf16; 2 or 3 = every matrix is a sum of that many bf16 planes (GemmProblem::*_plane strides).
-hipError_t launch_gemm_bf16(int coarse, int strips, const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
+constexpr int kGemmStrips = 1, kGemmPersistent = 2;
+hipError_t launch_gemm_bf16(int coarse, int flags, const GemmProblem* probs, const GemmTile* tiles, int n_tiles,
                             float beta_acc, float beta_e, int alpha_idx, float diag_add, int l_kmajor, int planes,
                             hipStream_t s);
 hipError_t launch_gemm_f32(const GemmProblem* probs, const GemmTile* tiles, int n_tiles,

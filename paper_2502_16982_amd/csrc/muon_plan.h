@@ -31,6 +31,9 @@ struct TileSet {
   size_t sym = 0, apply = 0, apply_last = 0;
   int n_sym = 0, n_apply = 0, n_apply_last = 0;
   bool strips = false;    // the tables hold 512 x 128 tiles (the launch then needs the larger LDS allocation)
+  // every problem of the launch has the same n_pad / m_pad, i.e. every tile of the Gram product / of the other two
+  // products runs a K loop of the same length: the launch can then deal its tiles to persistent blocks statically
+  bool uniform_n = false, uniform_m = false;
 };
 
 // Launch group: all matrices of one chunk.  Each product is one launch per level: the coarse launch (matrix-core
@@ -77,7 +80,8 @@ int plan_workspace_bytes(const muon_param* shapes, int32_t n, int32_t ns_dtype, 
 // MUON_E_WORKSPACE_TOO_SMALL or a validation status.  May throw std::bad_alloc.
 int plan_build(Plan& out, const muon_param* shapes, int32_t n, int32_t ns_dtype, uintptr_t ws_base, size_t ws_bytes);
 
-// Tile table of one grouped launch as records {matrix, first row, first column, rows, columns} in elements
+// Tile table of one grouped launch as records {matrix, first row, first column, rows, columns (in elements),
+// computed 32 x 32 blocks}
 // (see muon_plan_tiles).  Returns the number of records of the table.
 int64_t plan_tiles(const Plan& plan, int chunk, int product, int level, int32_t* out, int32_t cap_records);
 

@@ -75,9 +75,11 @@ struct GemmProblem {
 // block shapes (and tiles shifted to end at the matrix edge) share one table format.
 constexpr int kTileUnit = 64;
 // Block-tile shapes of the bf16 matrix-core kernel (the fp32 kernel has one 64 x 64 shape and ignores the field).
-enum GemmShape : int { kShape128 = 0, kShape256 = 1, kShape512x128 = 2, kNumShapes = 3 };
-constexpr int kShapeRows[kNumShapes] = {128, 256, 512};
-constexpr int kShapeCols[kNumShapes] = {128, 256, 128};
+// kShape256Diag: a 256 x 256 tile on the diagonal of a symmetric product (plain bf16 only), computed from its upper
+// triangle of 32 x 32 blocks.
+enum GemmShape : int { kShape128 = 0, kShape256 = 1, kShape512x128 = 2, kShape256Diag = 3, kNumShapes = 4 };
+constexpr int kShapeRows[kNumShapes] = {128, 256, 512, 256};
+constexpr int kShapeCols[kNumShapes] = {128, 256, 128, 256};
 constexpr int kF32Tile = 64;       // block tile of the fp32 Newton-Schulz GEMM
 constexpr int kTileDiagonal = 1;   // GemmTile::flags: tile on the diagonal of a symmetric product: it is its own mirror
                                    // image, so only one of the two stores is made
