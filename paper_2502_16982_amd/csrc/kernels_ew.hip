@@ -266,8 +266,12 @@ __global__ __launch_bounds__(256) void norm_finalize_kernel(const MatDesc* __res
 // ------------------------------------------------------------------------------------------------------
 // Where O (in W's orientation) lives after the Newton-Schulz phase.  o_sel bit 0: which of Xt[0..1] for matrices
 // iterated on their transpose; bit 1: X (0) or Xt[0] used as the second m_pad x n_pad buffer (1) for the others.
+// The record is read in place, never copied into a local: with a local copy the compiler turned the selections below
+// into loads from a selected address of that copy, which put the whole 128-byte record into per-thread scratch memory
+// - 8 bytes of scratch traffic per matrix element; the HBM-side write counter of the update kernel read twice the
+// bytes of W because of it.
 __device__ __forceinline__ const void* o_source(const MatDesc& d, int o_sel) {
-  if (d.transposed) return d.Xt[o_sel & 1];
+  if (d.transposed) return (o_sel & 1) ? d.Xt[1] : d.Xt[0];
   return (o_sel & 2) ? d.Xt[0] : d.X;
 }
 
@@ -405,7 +409,7 @@ __global__ __launch_bounds__(256) void apply_update_kernel(const MatDesc* __rest
                                                             int use_s) {
   __shared__ float red[4];
   const EwTile t = tiles[blockIdx.x];
-  const MatDesc d = mats[t.mat];
+  const MatDesc& d = mats[t.mat];     // read in place (uniform address: scalar loads); see o_source
   const MatPtrs pt = ptrs[t.mat];
   // factor that multiplies the stored O: the three variants of section 3.1 (Eq. 5-7)
   float scale;
@@ -430,7 +434,7 @@ __global__ __launch_bounds__(256) void update_sumsq_kernel(const MatDesc* __rest
                                                             int o_sel) {
   __shared__ float red[4];
   const EwTile t = tiles[blockIdx.x];
-  const MatDesc d = mats[t.mat];
+  const MatDesc& d = mats[t.mat];     // read in place (uniform address: scalar loads); see o_source
   const MatPtrs none{nullptr, nullptr, nullptr};
   for (int k = 0; k < t.count; ++k) {
     if (k) __syncthreads();
@@ -465,7 +469,7 @@ __global__ __launch_bounds__(256) void update_rms_kernel(const MatDesc* __restri
 template <typename XT, int PL, typename DT>
 __global__ __launch_bounds__(256) void read_update_kernel(const MatDesc* __restrict__ mats, int mat, int o_sel, int use_s,
                                                            DT* __restrict__ dst) {
-  const MatDesc d = mats[mat];
+  const MatDesc& d = mats[mat];
   const XT* o = static_cast<const XT*>(o_source(d, o_sel));
   const int pitch = d.transposed ? d.mp : d.np;
   const float s = use_s ? d.scal[0] : 1.f;
