@@ -49,7 +49,7 @@ def rel_fro(x: np.ndarray, ref: np.ndarray) -> float:
 # the norm at 4096 x 4096), so the error is also measured per BLOCK x BLOCK block of the output and per element:
 #  * per block: ||dO_blk||_F / max(||O_blk||_F, average block norm) <= BLOCK_FACTOR * tol.  Rounding errors of the
 #    iteration are spread over all entries (they live in singular directions, which are dense), so a block's relative
-#    error is the matrix's, within sampling noise; measured ratios block / whole are 1.0-1.3.  A 32 x 32 sub-tile that
+#    error is the matrix's, within sampling noise; measured ratios block / whole are 1.0-1.45.  A 32 x 32 sub-tile that
 #    is garbage (100 % error on 1/16 of a block) gives 0.25, twelve times the 2e-2 bar and six times this one.
 #  * per element: |dO_ij| <= ELEM_FACTOR * tol * max(|O_ij|, RMS(O)).  For errors of standard deviation tol * RMS(O) the
 #    largest of 1e8 entries is below 6 standard deviations; entries far above the RMS (gradient outliers put a few
