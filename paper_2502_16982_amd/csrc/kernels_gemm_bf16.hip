@@ -138,9 +138,15 @@ constexpr int seg_plane(int pl, int s, int which) {
 // LKM: the L operand is stored K-major (element (i, k) at L[k * ldl + i], i.e. the product is L^T-by-R^T of two
 // row-major arrays); its MFMA fragments then come from LDS through the transposing read ds_read_b64_tr_b16.
 // PL: number of bf16 planes per matrix (1: plain bf16).
+__device__ __forceinline__ int thread_index(int wave_id) {
+  unsigned zero = 0;
+  asm volatile("" : "+v"(zero));                 // opaque, so that the lane count below is redone where it is used
+  return (wave_id << 6) | (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, zero));
+}
+
 template <int BM, int BN, int WM_, int WN_, int NSTAGE, bool LKM, int PL>
 __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmTile& tile, unsigned char* smem, float beta_acc,
-                                               float beta_e, int alpha_idx, float diag_add) {
+                                               float beta_e, int alpha_idx, float diag_add, int wave_id) {
   constexpr int NW = WM_ * WN_, NT = NW * 64;
   constexpr int WTM = BM / WM_, WTN = BN / WN_;    // wave tile
   constexpr int FM = WTM / 32, FN = WTN / 32;      // 32x32 MFMA tiles per wave
@@ -156,8 +162,11 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
 
   // The thread index is made opaque once per tile: everything below that derives from it (lane addresses, swizzle
   // keys) is then recomputed for every tile of a persistent block instead of being hoisted out of the tile loop, where
-  // it would occupy registers for the whole kernel and push the epilogues into scratch.
-  int tid = threadIdx.x;
+  // it would occupy registers for the whole kernel and push the epilogues into scratch.  It is put together from the
+  // wave's number (a scalar the kernel keeps) and the lane's position, not taken from the register the hardware
+  // delivers it in: that one does not survive a tile, and fetching a saved copy from scratch would mean waiting for
+  // vector memory, i.e. for every store of the block's previous tile.
+  int tid = thread_index(wave_id);
   asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1076,8 +1085,8 @@ __device__ __forceinline__ void diag_wave_body(const GemmProblem& p, int row0, u
 }
 
 __device__ __forceinline__ void diag_tile_body(const GemmProblem& p, const GemmTile& tile, unsigned char* smem, float beta_acc,
-                                               float beta_e, int alpha_idx, float diag_add) {
-  int tid = threadIdx.x;
+                                               float beta_e, int alpha_idx, float diag_add, int wave_id) {
+  int tid = thread_index(wave_id);
   asm volatile("" : "+v"(tid));                  // see gemm_tile_body
   const int row0 = tile.r0 * kTileUnit;
   switch (__builtin_amdgcn_readfirstlane(tid >> 6)) {
@@ -1098,14 +1107,31 @@ constexpr size_t kLds256 = TileCfg<256, 256>::lds_bytes(2);
 constexpr size_t kLds512 = TileCfg<512, 128>::lds_bytes(2);
 constexpr int kMaxPlanes = 3;
 
+// A table entry through whole-dword loads, so that they are scalar loads: the sub-dword fields would otherwise come
+// through a vector load, and the wait for it is a wait for every store of the block's previous tile as well.
+__device__ __forceinline__ GemmTile load_tile(const GemmTile* __restrict__ tiles, int t) {
+  static_assert(sizeof(GemmTile) == 12, "three dwords");
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(tiles) + 3 * (size_t)t;
+  const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+  GemmTile r;
+  r.prob = (int32_t)w0;
+  r.r0 = (uint16_t)(w1 & 0xffffu);
+  r.c0 = (uint16_t)(w1 >> 16);
+  r.shape = (uint8_t)(w2 & 0xffu);
+  r.flags = (uint8_t)((w2 >> 8) & 0xffu);
+  r.pad_ = 0;
+  return r;
+}
+
 template <bool LKM, int PL>
 __global__ __launch_bounds__(256, 2) void ns_gemm_bf16_fine_kernel(const GemmProblem* __restrict__ probs,
                                                                     const GemmTile* __restrict__ tiles, float beta_acc,
                                                                     float beta_e, int alpha_idx, float diag_add) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const GemmTile tile = tiles[blockIdx.x];
+  const GemmTile tile = load_tile(tiles, blockIdx.x);
   const GemmProblem p = probs[tile.prob];
-  gemm_tile_body<128, 128, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+  gemm_tile_body<128, 128, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add,
+                                             __builtin_amdgcn_readfirstlane(threadIdx.x >> 6));
 }
 
 // Block b works through table entries b, b + gridDim.x, ...  Launched with one block per tile, or persistent: one
@@ -1118,16 +1144,17 @@ __global__ __launch_bounds__(256, 1) void ns_gemm_bf16_kernel(const GemmProblem*
                                                                const GemmTile* __restrict__ tiles, int n_tiles, float beta_acc,
                                                                float beta_e, int alpha_idx, float diag_add) {
   extern __shared__ __align__(16) unsigned char smem[];
+  const int wave_id = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-    const GemmTile tile = tiles[t];
+    const GemmTile tile = load_tile(tiles, t);
     const GemmProblem p = probs[tile.prob];
     const int shape = __builtin_amdgcn_readfirstlane(tile.shape);
     if (shape == kShape512x128) {
-      gemm_tile_body<512, 128, 4, 1, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+      gemm_tile_body<512, 128, 4, 1, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add, wave_id);
     } else if (!LKM && PL == 1 && shape == kShape256Diag) {
-      if constexpr (!LKM && PL == 1) diag_tile_body(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+      if constexpr (!LKM && PL == 1) diag_tile_body(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add, wave_id);
     } else {
-      gemm_tile_body<256, 256, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add);
+      gemm_tile_body<256, 256, 2, 2, 2, LKM, PL>(p, tile, smem, beta_acc, beta_e, alpha_idx, diag_add, wave_id);
     }
     __syncthreads();        // every wave has read its part of the LDS images: the next tile may overwrite them
   }
