@@ -227,13 +227,17 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
   const int fkey = (fr >> 1) & 7;
   const int a_base = (wm * WTM + fr) * ROWB, b_base = BM * ROWB + (wn * WTN + fr) * ROWB;
 
+  // The zero the accumulators start from is opaque to the compiler: a constant 16-register tuple would be hoisted
+  // out of a persistent block's tile loop, find no register there and come back from scratch at every tile.
+  float acc0 = 0.f;
+  asm volatile("" : "+v"(acc0));
   f32x16 acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = acc0;
 
   // K-major L: the 16 lanes of a group (g = lane/16) each address 8 bytes of a 4 (k) x 16 (i) block - lane l: k-row
   // l/4, columns 4*(l%4)..+3 - and each receives one column's 4 consecutive k values; two such reads make the 8
@@ -884,11 +888,13 @@ __device__ __forceinline__ void diag_wave_body(const GemmProblem& p, int row0, u
   };
   const int fr = lane & 31, fh = lane >> 5;
   const int fkey = (fr >> 1) & 7;
+  float acc0 = 0.f;
+  asm volatile("" : "+v"(acc0));                 // see gemm_tile_body
   f32x16 acc[N];
 #pragma unroll
   for (int t = 0; t < N; ++t)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+    for (int v = 0; v < 16; ++v) acc[t][v] = acc0;
   bf16x8 fg[KSTEPS][NF];
   auto read_frag = [&](int stage, int kk, int f) {
     fg[kk][f] = *reinterpret_cast<const bf16x8*>(smem + stage * STAGE_B + (32 * W::fb[f] + fr) * ROWB + (((2 * kk + fh) ^ fkey) * 16));
