@@ -224,7 +224,8 @@ def time_workload(name, steps, warmup, max_ws_gib, dev, ns_dtype=None):
     st.close()
     del tensors
     torch.cuda.empty_cache()
-    return {"wl": wl, "hyper": h, "bf16": bf16, "planes": planes, "elapsed": elapsed, "ms_per_step": ms_per_step, "nominal": nominal,
+    return {"wl": wl, "hyper": h, "bf16": bf16, "planes": planes, "steps": steps, "elapsed": elapsed, "ms_per_step": ms_per_step,
+            "nominal": nominal,
             "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
             "executed": executed, "gemm_ms": gemm_ms, "prof": prof, "roofline": roofline, "elementwise": ew, "n_el": n_el,
             "chunks": chunks, "workspace_bytes": ws_bytes}
@@ -309,8 +310,9 @@ def main() -> int:
                 "ms_per_step_median": o["ms_per_step_median"], "steps_per_s": 1e3 / o["ms_per_step"],
                 "ns_gemm_tflops_nominal": o["roofline"]["achieved"],
                 "matrix_core_tflops_executed": o["roofline"]["executed_tflops"],
-                "avg_gemm_launch_ms": o["roofline"]["avg_launch_ms"], "elementwise": o["elementwise"],
-                "workspace_bytes": o["workspace_bytes"], "chunks": o["chunks"]}
+                "avg_gemm_launch_ms": o["roofline"]["avg_launch_ms"], "roofline": o["roofline"],
+                "kernel_ms_per_step": {k: v[0] / o["steps"] for k, v in o["prof"].items() if v[1]},
+                "elementwise": o["elementwise"], "workspace_bytes": o["workspace_bytes"], "chunks": o["chunks"]}
     out["adamw_non_matrix_params"] = bench_adamw(dev)
     torch.cuda.empty_cache()
     if bf16:
