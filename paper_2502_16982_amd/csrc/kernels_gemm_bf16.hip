@@ -1190,6 +1190,8 @@ void launch_one(int coarse, int flags, const GemmProblem* probs, const GemmTile*
 
 }  // namespace
 
+int gemm_coarse_blocks() { return g_coarse_grid; }
+
 hipError_t gemm_setup() {
   int dev = 0, cus = 0;
   hipError_t e = hipGetDevice(&dev);

@@ -294,6 +294,19 @@ int build_context(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t n
   ctx->ns_dtype = ns_dtype;
   ctx->ws = static_cast<unsigned char*>(workspace);
   ctx->ws_bytes = workspace_bytes;
+  {
+    size_t least = 0;                // rejected before the device is touched
+    st = plan_workspace_bytes(shapes, n, ns_dtype, 1, &least);
+    if (st != MUON_OK) return st;
+    if (workspace_bytes < least) return MUON_E_WORKSPACE_TOO_SMALL;
+  }
+  if (upload) {
+    // before the plan: it evens out the persistent launches against the device's number of compute units
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = gemm_setup();
+    if (e != hipSuccess) return hip_fail(e);
+    ctx->plan.coarse_blocks = gemm_coarse_blocks();
+  }
   st = plan_build(ctx->plan, shapes, n, ns_dtype, reinterpret_cast<uintptr_t>(workspace), workspace_bytes);
   if (st != MUON_OK) return st;
   ctx->d_mats = reinterpret_cast<MatDesc*>(ctx->ws + ctx->plan.off_mats);
@@ -301,9 +314,7 @@ int build_context(muon_ctx** out, const muon_param* shapes, int32_t n, int32_t n
   if (!upload) {
     ctx->plan_only = true;
   } else {
-    hipError_t e = hipGetDevice(&ctx->device);
-    if (e == hipSuccess) e = gemm_setup();
-    if (e == hipSuccess) e = hipMemcpy(ctx->ws, ctx->plan.image.data(), ctx->plan.image.size(), hipMemcpyHostToDevice);
+    hipError_t e = hipMemcpy(ctx->ws, ctx->plan.image.data(), ctx->plan.image.size(), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&ctx->h_ptrs_pinned), sizeof(MatPtrs) * (size_t)n, hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->upload_done, hipEventDisableTiming);
     if (e != hipSuccess) return hip_fail(e);
@@ -409,6 +420,7 @@ int step_static_impl(const muon_param* params, int32_t n, int32_t ns_dtype, cons
     ctx->device = dev;
     ctx->ws = slot.ptr;
     ctx->ws_bytes = kStaticScratchBytes;
+    ctx->plan.coarse_blocks = gemm_coarse_blocks();
     st = plan_build(ctx->plan, params, n, ns_dtype, reinterpret_cast<uintptr_t>(slot.ptr), kStaticScratchBytes);
     if (st != MUON_OK) return st;
     if (ctx->plan.chunks.size() != 1) return MUON_E_STATIC_LIMIT;

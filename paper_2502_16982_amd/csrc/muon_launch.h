@@ -8,6 +8,8 @@ namespace muon {
 
 // One-time per-process kernel attribute setup (large dynamic LDS).  Returns a hipError_t.
 hipError_t gemm_setup();
+// Blocks of a persistent coarse GEMM launch = compute units of the device gemm_setup ran on (0 before it).
+int gemm_coarse_blocks();
 
 // a1-a3: momentum, sum of squares, cast + orient.  both_layouts != 0: U goes to X and Xt[0] (one holds U, the other
 // U^T); 0: only X (the orientation with rows <= cols) is written.  One block per EwTile.

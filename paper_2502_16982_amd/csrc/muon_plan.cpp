@@ -65,6 +65,39 @@ void strip_tiles(int32_t prob, int rows, int col0, std::vector<GemmTile>& out, s
   cuts.push_back((int)out.size());
 }
 
+// A persistent launch (one block per compute unit striding through the table) gives every block the same number of
+// tiles only if the table length is a multiple of the number of blocks; the r tiles beyond that cost the launch a whole
+// extra round.  When r is small they are taken out of the coarse lists - plain 256 x 256 tiles from the end of the
+// problems that come last in the launch order - and handed to the fine launch, four 128 x 128 tiles each, where they
+// run side by side, one per compute unit.  `moved` receives them per problem; returns how many were moved.
+constexpr int kMaxMovedTiles = 64;
+size_t move_tail_to_fine(const std::vector<int>& order, std::vector<std::vector<GemmTile>>& lists,
+                         std::vector<std::vector<int>>& cuts, int blocks, std::vector<std::vector<GemmTile>>& moved) {
+  size_t total = 0;
+  for (const auto& l : lists) total += l.size();
+  if (blocks <= 0 || total <= (size_t)blocks) return 0;
+  const size_t r = total % (size_t)blocks;
+  if (r == 0 || r > (size_t)kMaxMovedTiles) return 0;
+  size_t plain = 0;
+  for (const auto& l : lists)
+    for (const GemmTile& t : l) plain += (t.shape == kShape256 && !(t.flags & kTileDiagonal)) ? 1 : 0;
+  if (plain < r) return 0;
+  size_t left = r;
+  for (size_t oi = order.size(); oi-- > 0 && left > 0;) {
+    std::vector<GemmTile>& l = lists[order[oi]];
+    for (size_t i = l.size(); i-- > 0 && left > 0;)
+      if (l[i].shape == kShape256 && !(l[i].flags & kTileDiagonal)) {
+        moved[order[oi]].push_back(l[i]);
+        l.erase(l.begin() + (std::ptrdiff_t)i);
+        --left;
+      }
+    // block boundaries are list positions: those past the shortened list go
+    std::vector<int>& c = cuts[order[oi]];
+    while (!c.empty() && c.back() > (int)l.size()) c.pop_back();
+  }
+  return r;
+}
+
 size_t deal_tiles(const std::vector<int>& order, const std::vector<std::vector<GemmTile>>& per_problem,
                   const std::vector<std::vector<int>>& per_problem_cuts, const std::vector<int64_t>& weight, GemmTile* out) {
   std::vector<std::vector<GemmTile>> seq(kXcds);
@@ -425,6 +458,12 @@ int plan_build(Plan& plan, const muon_param* shapes, int32_t n, int32_t ns_dtype
       }
       // tile tables: level 1 = 256 x 256 tiles and 512 x 128 strip tiles (matrix cores only), level 0 = what they
       // leave uncovered, in fine tiles
+      bool uniform_n = true, uniform_m = true;
+      for (size_t k = 0; k < np_; ++k) {
+        if (w_n[k] != w_n[0]) uniform_n = false;
+        if (w_m[k] != w_m[0]) uniform_m = false;
+      }
+      std::vector<std::vector<GemmTile>> moved_sym(np_), moved_app(np_);   // coarse tiles handed to the fine level
       for (int level = 1; level >= 0; --level) {
         if (level == 1 && !mc) continue;
         std::vector<std::vector<GemmTile>> sym(np_), app(np_);
@@ -454,17 +493,33 @@ int plan_build(Plan& plan, const muon_param* shapes, int32_t n, int32_t ns_dtype
             blocked_tiles((int32_t)k, q.tile, fine_shape, tm, tm, true, cm * r, cm * r, sym_strip ? tm - 1 : -1, sym[k], sym_cuts[k]);
             if (mc) blocked_tiles((int32_t)k, q.tile, fine_shape, tn, tm, false, cn * r, cm * r, app_strip ? tm - 1 : -1, app[k], app_cuts[k], 8, 4);
             else blocked_tiles((int32_t)k, q.tile, fine_shape, tm, tn, false, 0, 0, -1, app[k], app_cuts[k]);
+            // the coarse tiles moved here: four fine tiles each (never a diagonal tile, so none of the four is one)
+            for (int which = 0; which < 2; ++which) {
+              const std::vector<GemmTile>& mv = which ? moved_app[k] : moved_sym[k];
+              std::vector<GemmTile>& dst = which ? app[k] : sym[k];
+              std::vector<int>& dcuts = which ? app_cuts[k] : sym_cuts[k];
+              for (const GemmTile& t : mv) {
+                for (int dr = 0; dr < r; ++dr)
+                  for (int dc = 0; dc < r; ++dc)
+                    dst.push_back(make_tile((int32_t)k, t.r0 * kTileUnit + dr * q.tile, t.c0 * kTileUnit + dc * q.tile, fine_shape, 0));
+                dcuts.push_back((int)dst.size());
+              }
+            }
           }
+        }
+        if (level == 1) {
+          // launches whose tiles all run the same K are persistent: even out their last round
+          if (uniform_n && uniform_m) move_tail_to_fine(by_n, sym, sym_cuts, plan.coarse_blocks, moved_sym);
+          if (uniform_m) move_tail_to_fine(by_m, app, app_cuts, plan.coarse_blocks, moved_app);
+        }
+        for (size_t k = 0; k < np_; ++k) {
           n_sym += sym[k].size();
           n_app += app[k].size();
         }
         TileSet& ts = level ? g.coarse : g.fine;
         ts.strips = strips;
-        ts.uniform_n = ts.uniform_m = true;
-        for (size_t k = 0; k < np_; ++k) {
-          if (w_n[k] != w_n[0]) ts.uniform_n = false;
-          if (w_m[k] != w_m[0]) ts.uniform_m = false;
-        }
+        ts.uniform_n = uniform_n;
+        ts.uniform_m = uniform_m;
         ts.sym = take(n_sym * sizeof(GemmTile));
         ts.apply = take(n_app * sizeof(GemmTile));
         ts.apply_last = take(n_app * sizeof(GemmTile));

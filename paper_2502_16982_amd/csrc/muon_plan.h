@@ -61,6 +61,7 @@ struct Plan {
   std::vector<Chunk> chunks;
   std::vector<unsigned char> image;   // host image of the table region (what muon_init uploads)
   size_t off_mats = 0, off_ptrs = 0;  // byte offsets of the matrix records and of the per-step pointer table
+  int coarse_blocks = 256;            // blocks of a persistent coarse launch (compute units of the device); set before plan_build
 };
 
 constexpr int kCoarse = 256;          // block tile of the large bf16 kernel

@@ -11,6 +11,8 @@ SHAPE_SETS = {
     "tiles256": [(1024, 1024), (1024, 1536), (1280, 1024), (384, 640), (640, 1152)],
     "moe_expert": [(2048, 1408), (2048, 1408), (1408, 2048)],
     "block": [(4096, 4096), (4096, 11008), (11008, 4096)],
+    # the whole 4096-wide block: its 3088 apply tiles are 12 x 256 + 16, so 16 of them move to the fine launch
+    "block_full": [(4096, 4096)] * 4 + [(4096, 11008)] * 2 + [(11008, 4096)],
     "many_small": [(256, 384)] * 40 + [(384, 256)] * 30,
     "extreme": [(4, 1 << 20), (1 << 20, 4), (1, 70000)],
 }
@@ -163,6 +165,36 @@ def closed_form_executed_flops(m, n):
     sym_area = cm * (cm - 1) // 2 * 256 * 256 + cm * 36 * 1024 + odd * -(-m // 512) * 512 * 128
     app_area = cn * cm * 256 * 256 + odd * -(-n // 512) * 512 * 128 + ((n // 128) % 2) * 2 * cm * 128 * 128
     return 2 * (sym_area * n + sym_area * m + app_area * m)
+
+
+def test_last_round_of_a_persistent_launch_goes_to_the_fine_launch():
+    """Launches whose tiles all run the same K are persistent, one block per compute unit (256 when no device is
+    asked): when the table is a few tiles longer than a multiple of that, those tiles are issued as four 128 x 128
+    tiles each in the fine launch, and every block of the coarse launch gets the same number of tiles."""
+    shapes = SHAPE_SETS["block_full"]
+    ctx, _ = plan(shapes, binding.MUON_BF16)
+    try:
+        coarse = binding.muon_plan_tiles(ctx, 0, "apply", 1)
+        fine = binding.muon_plan_tiles(ctx, 0, "apply", 0)
+        assert len(coarse) == 3072 and len(fine) == 64
+        assert all(t[3:5] == (128, 128) for t in fine)
+        # whole 256 x 256 tiles: the four quarters of each moved tile are all there
+        corners = {(t[0], t[1] // 256, t[2] // 256) for t in fine}
+        assert len(corners) == 16
+        for m, i, j in corners:
+            assert {(m, 256 * i + a, 256 * j + b) for a in (0, 128) for b in (0, 128)} <= {t[:3] for t in fine}
+        # the symmetric launches mix K = 4096 and K = 11008 in the Gram product: not persistent, nothing moved
+        assert len(binding.muon_plan_tiles(ctx, 0, "gram", 1)) == 7 * 136
+        assert len(binding.muon_plan_tiles(ctx, 0, "gram", 0)) == 0
+    finally:
+        binding.lib().muon_destroy(ctx)
+    # 96 tiles over a multiple of 256 are too many to be worth a second launch: left alone
+    ctx, _ = plan(SHAPE_SETS["block"], binding.MUON_BF16)
+    try:
+        assert len(binding.muon_plan_tiles(ctx, 0, "apply", 1)) == 1632
+        assert len(binding.muon_plan_tiles(ctx, 0, "apply", 0)) == 0
+    finally:
+        binding.lib().muon_destroy(ctx)
 
 
 @pytest.mark.parametrize("name", ["dense12_w1024", "block_w4096", "moe_bank_66x2048x1408"])
