@@ -276,8 +276,11 @@ __device__ __forceinline__ void gemm_tile_body(const GemmProblem& p, const GemmT
   // one for everything at the end of phase B.  The LDS returns data in issue order.  Every wait is an asm statement
   // that takes the fragment registers it covers as read-write operands (land_kstep below): to the compiler the
   // wait produces those values, so every MFMA that consumes a fragment depends on the wait that covers it and
-  // reads the registers the wait names - it cannot be moved ahead of the wait, nor fed from a copy or a spill slot
-  // made before the data landed.
+  // reads the registers the wait names - it cannot be moved ahead of the wait.  What the source cannot forbid is a
+  // compiler-made copy or spill of a read's destination between the read and its wait; the generated code is
+  // therefore checked at every build of the tests (tests/test_kmajor_asm_hazards.py walks the control-flow graph of
+  // the compiled kernels and fails if any instruction touches the destination of an LDS read that no wait has
+  // retired yet).
   u32x2 km_half[KSTEPS][FM][2];
   u32x4 km_b[KSTEPS][FN];
   auto read_one = [&](int stage, int kk, int r) {
