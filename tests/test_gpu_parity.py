@@ -441,6 +441,17 @@ def test_gradient_scale_invariance(dev, ns, g_std, eps):
         assert r["o_finite"] and r["o_rel_fro"] <= tol and r["m_err"] <= U.TOL_ELEM, r
 
 
+def test_last_round_of_a_persistent_launch_in_the_fine_launch(dev):
+    """26 matrices of 1024 x 1024: the symmetric launches have 26 x 10 = 256 + 4 tiles of equal K, so they are
+    persistent and the planner issues the last 4 plain tiles (of the last matrices) as sixteen 128 x 128 tiles in the
+    fine launch; 64 x (1024 x 2048) does the same to the apply product (64 x 32 = 2048 tiles: nothing left over) and
+    65 of them leave 32 over.  Every matrix that can hold a moved tile is compared with the oracle."""
+    wl = workloads.custom("sym_tail", [(1024, 1024)] * 26, seed_base=91)
+    assert_records(U.run_and_compare(wl, dev, check=[0, 23, 24, 25]), U.TOL_BF16_FRO)
+    wl = workloads.custom("apply_tail", [(1024, 2048)] * 65, seed_base=92)
+    assert_records(U.run_and_compare(wl, dev, check=[0, 62, 63, 64]), U.TOL_BF16_FRO)
+
+
 def test_lr_zero_leaves_weights_bitwise(dev):
     wl = workloads.custom("lr0", [(100, 300)], seed_base=31)
     (w, g, m), = workloads.make_all(wl, dev)

@@ -14,6 +14,8 @@ SHAPE_SETS = {
     # the whole 4096-wide block: its 3088 apply tiles are 12 x 256 + 16, so 16 of them move to the fine launch
     "block_full": [(4096, 4096)] * 4 + [(4096, 11008)] * 2 + [(11008, 4096)],
     "many_small": [(256, 384)] * 40 + [(384, 256)] * 30,
+    # 26 x 10 symmetric tiles = 256 + 4 and 26 x 16 apply tiles = 256 + 160: the 4 go to the fine launch, the 160 stay
+    "sym_tail": [(1024, 1024)] * 26,
     "extreme": [(4, 1 << 20), (1 << 20, 4), (1, 70000)],
 }
 
