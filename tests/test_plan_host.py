@@ -27,28 +27,26 @@ def plan(shapes, ns, max_bytes=0):
     return binding.muon_plan_only(p, n, ns, need), p
 
 
-@pytest.mark.parametrize("ns", [binding.MUON_BF16, binding.MUON_BF16X2, binding.MUON_F32])
-@pytest.mark.parametrize("name", sorted(SHAPE_SETS))
-def test_every_output_tile_is_computed(name, ns):
+def assert_full_coverage(ctx, shapes, ns, label=""):
     """Every output cell of every product is covered by a tile; a cell is covered twice only where the last
-    512 x 128 tile of a column strip was shifted to end at the matrix edge (both tiles then write the same values)."""
-    shapes = SHAPE_SETS[name]
-    ctx, _ = plan(shapes, ns)
-    try:
-        assert binding.muon_plan_chunks(ctx) == 1
-        desc = [binding.muon_plan_describe(ctx, i) for i in range(len(shapes))]
-        mc = ns != binding.MUON_F32
-        for product in ("gram", "poly", "apply", "apply_last"):
-            sym = product in ("gram", "poly")
-            cover, strip_cover = {}, {}
-            for i, d in enumerate(desc):
-                fine = d["tile_n"]
-                tm, tn = d["m_pad"] // fine, d["n_pad"] // fine
-                # output grid in fine cells: m x m for the symmetric products; X'^T (n x m) on the matrix cores, X' else
-                cover[i] = np.zeros((tm, tm) if sym else ((tn, tm) if mc else (tm, tn)), dtype=np.int32)
-                strip_cover[i] = np.zeros_like(cover[i])
+    512 x 128 tile of a column strip was shifted to end at the matrix edge (both tiles then write the same values).
+    Works over all chunks of the plan: a matrix's tiles are all in the chunk the plan puts it in."""
+    desc = [binding.muon_plan_describe(ctx, i) for i in range(len(shapes))]
+    mc = ns != binding.MUON_F32
+    chunks = binding.muon_plan_chunks(ctx)
+    for product in ("gram", "poly", "apply", "apply_last"):
+        sym = product in ("gram", "poly")
+        cover, strip_cover = {}, {}
+        for i, d in enumerate(desc):
+            fine = d["tile_n"]
+            tm, tn = d["m_pad"] // fine, d["n_pad"] // fine
+            # output grid in fine cells: m x m for the symmetric products; X'^T (n x m) on the matrix cores, X' else
+            cover[i] = np.zeros((tm, tm) if sym else ((tn, tm) if mc else (tm, tn)), dtype=np.int32)
+            strip_cover[i] = np.zeros_like(cover[i])
+        for chunk in range(chunks):
             for level in (0, 1):
-                for mat, r0, c0, rows, cols, blocks in binding.muon_plan_tiles(ctx, 0, product, level):
+                for mat, r0, c0, rows, cols, blocks in binding.muon_plan_tiles(ctx, chunk, product, level):
+                    assert desc[mat]["chunk"] == chunk
                     fine = desc[mat]["tile_n"]
                     if not mc:
                         assert level == 0 and (rows, cols) == (64, 64)
@@ -69,21 +67,56 @@ def test_every_output_tile_is_computed(name, ns):
                     if (rows, cols) == (512, 128):
                         assert c0 + cols == grid.shape[1] * fine    # strips are the last 128 columns
                         strip_cover[mat][sl] += 1
-            for i, grid in cover.items():
-                twice = grid > 1
-                assert (grid[twice] == 2).all() and (strip_cover[i][twice] == 2).all(), (name, product, shapes[i])
-                assert twice.sum() <= 3, (name, product, shapes[i])    # at most one shifted tile: < 512 rows of overlap
-                if sym:
-                    upper = np.triu(np.ones_like(grid))
-                    assert (grid[upper == 1] >= 1).all(), (name, product, shapes[i])
-                    # below the diagonal only what a diagonal 256-tile computes along with its upper part
-                    r = 256 // desc[i]["tile_n"] if mc else 1
-                    blocks_i, blocks_j = np.nonzero(np.tril(grid, -1))
-                    assert all(bi // r == bj // r for bi, bj in zip(blocks_i, blocks_j)), (name, product, shapes[i])
-                else:
-                    assert (grid >= 1).all(), (name, product, shapes[i])
+        for i, grid in cover.items():
+            twice = grid > 1
+            assert (grid[twice] == 2).all() and (strip_cover[i][twice] == 2).all(), (label, product, shapes[i])
+            assert twice.sum() <= 3, (label, product, shapes[i])    # at most one shifted tile: < 512 rows of overlap
+            if sym:
+                upper = np.triu(np.ones_like(grid))
+                assert (grid[upper == 1] >= 1).all(), (label, product, shapes[i])
+                # below the diagonal only what a diagonal 256-tile computes along with its upper part
+                r = 256 // desc[i]["tile_n"] if mc else 1
+                blocks_i, blocks_j = np.nonzero(np.tril(grid, -1))
+                assert all(bi // r == bj // r for bi, bj in zip(blocks_i, blocks_j)), (label, product, shapes[i])
+            else:
+                assert (grid >= 1).all(), (label, product, shapes[i])
+
+
+@pytest.mark.parametrize("ns", [binding.MUON_BF16, binding.MUON_BF16X2, binding.MUON_F32])
+@pytest.mark.parametrize("name", sorted(SHAPE_SETS))
+def test_every_output_tile_is_computed(name, ns):
+    shapes = SHAPE_SETS[name]
+    ctx, _ = plan(shapes, ns)
+    try:
+        assert binding.muon_plan_chunks(ctx) == 1
+        assert_full_coverage(ctx, shapes, ns, name)
     finally:
         binding.lib().muon_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shape_lists_are_covered_in_every_chunking(seed):
+    """Seeded random lists (dimensions from 1 to 3000, many of them multiples of 128 or 256 so that strips, moved
+    tiles and fine leftovers all occur; sometimes many copies of one shape, which makes the launches persistent),
+    planned once with room for everything and once with a workspace that forces several chunks."""
+    rng = np.random.RandomState(1000 + seed)
+    def dim():
+        k = rng.randint(4)
+        return int(rng.randint(1, 3000)) if k == 0 else int(128 * rng.randint(1, 24)) if k == 1 else int(256 * rng.randint(1, 12)) if k == 2 else int(64 * rng.randint(1, 40))
+    shapes = [(dim(), dim()) for _ in range(int(rng.randint(1, 10)))]
+    if seed % 3 == 0:
+        shapes += [(int(256 * rng.randint(2, 6)), int(256 * rng.randint(2, 6)))] * int(rng.randint(20, 70))
+    ns = [binding.MUON_BF16, binding.MUON_BF16X2, binding.MUON_F32][seed % 3 if seed % 3 != 0 else 0]
+    n = len(shapes)
+    p = binding.param_array(shapes, [1] * n, [1] * n)
+    full = binding.muon_workspace_bytes(p, n, ns, 0)
+    least = binding.muon_workspace_bytes(p, n, ns, 1)
+    for ws in (full, least + (full - least) // 3):
+        ctx = binding.muon_plan_only(p, n, ns, ws)
+        try:
+            assert_full_coverage(ctx, shapes, ns, "random%d" % seed)
+        finally:
+            binding.lib().muon_destroy(ctx)
 
 
 def test_orientation_padding_and_tile_sizes():
