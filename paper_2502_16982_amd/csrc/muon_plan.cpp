@@ -98,8 +98,14 @@ size_t move_tail_to_fine(const std::vector<int>& order, std::vector<std::vector<
   return r;
 }
 
+// `slots` > 0 (coarse tables; the compute units of a die): a persistent launch gives the block in slot c of a die the
+// entries c, c + slots, c + 2 slots, ... of that die's sequence.  Tiles differ in cost (a diagonal tile issues 9/16
+// of the MFMAs of a full one), so within every run of `slots` entries - the tiles the die runs at the same time,
+// whose set stays as it is - the tiles are handed to the slots most expensive first, each to the slot that has
+// accumulated least so far.
 size_t deal_tiles(const std::vector<int>& order, const std::vector<std::vector<GemmTile>>& per_problem,
-                  const std::vector<std::vector<int>>& per_problem_cuts, const std::vector<int64_t>& weight, GemmTile* out) {
+                  const std::vector<std::vector<int>>& per_problem_cuts, const std::vector<int64_t>& weight, GemmTile* out,
+                  int slots = 0) {
   std::vector<std::vector<GemmTile>> seq(kXcds);
   std::vector<int64_t> load(kXcds, 0);
   int rr = 0;
@@ -136,6 +142,28 @@ size_t deal_tiles(const std::vector<int>& order, const std::vector<std::vector<G
         seq[x].insert(seq[x].end(), tiles.begin() + c0, tiles.begin() + c1);
         seq[x].insert(seq[x].end(), tiles.begin() + lo, tiles.begin() + c0);
         seq[x].insert(seq[x].end(), tiles.begin() + c1, tiles.begin() + hi);
+      }
+    }
+  }
+  if (slots > 0) {
+    // cost in units of K: the MFMA work of the main loop plus a fixed part for the first slabs and the epilogue
+    auto cost = [&](const GemmTile& t) {
+      const int64_t blocks = t.shape == kShape256Diag ? 36 : (int64_t)kShapeRows[t.shape] * kShapeCols[t.shape] / 1024;
+      return (int64_t)512 + weight[t.prob] * blocks / 64;
+    };
+    for (auto& q : seq) {
+      std::vector<int64_t> acc((size_t)slots, 0);
+      for (size_t r0 = 0; r0 < q.size(); r0 += (size_t)slots) {
+        const size_t cnt = std::min((size_t)slots, q.size() - r0);
+        std::vector<GemmTile> round(q.begin() + (std::ptrdiff_t)r0, q.begin() + (std::ptrdiff_t)(r0 + cnt));
+        std::stable_sort(round.begin(), round.end(), [&](const GemmTile& a, const GemmTile& b) { return cost(a) > cost(b); });
+        std::vector<size_t> slot(cnt);
+        std::iota(slot.begin(), slot.end(), (size_t)0);
+        std::stable_sort(slot.begin(), slot.end(), [&](size_t a, size_t b) { return acc[a] < acc[b]; });
+        for (size_t i = 0; i < cnt; ++i) {
+          q[r0 + slot[i]] = round[i];
+          acc[slot[i]] += cost(round[i]);
+        }
       }
     }
   }
@@ -524,9 +552,13 @@ int plan_build(Plan& plan, const muon_param* shapes, int32_t n, int32_t ns_dtype
         ts.apply = take(n_app * sizeof(GemmTile));
         ts.apply_last = take(n_app * sizeof(GemmTile));
         // the two symmetric products share one table, dealt in the order of the Gram product (K = n)
-        ts.n_sym = (int)deal_tiles(by_n, sym, sym_cuts, w_n, reinterpret_cast<GemmTile*>(img.data() + ts.sym));
-        ts.n_apply = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply));
-        ts.n_apply_last = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply_last));
+        // costs are evened out over a die's blocks only in tables whose launches are all persistent: where the
+        // hardware hands out the blocks (mixed K) the plain order measured better
+        const int slots = level == 1 ? plan.coarse_blocks / kXcds : 0;
+        const int sym_slots = uniform_n && uniform_m ? slots : 0, app_slots = uniform_m ? slots : 0;
+        ts.n_sym = (int)deal_tiles(by_n, sym, sym_cuts, w_n, reinterpret_cast<GemmTile*>(img.data() + ts.sym), sym_slots);
+        ts.n_apply = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply), app_slots);
+        ts.n_apply_last = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply_last), app_slots);
       }
       ch.groups.push_back(g);
     }
