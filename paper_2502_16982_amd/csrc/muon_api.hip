@@ -206,7 +206,7 @@ int enqueue_step(muon_ctx* ctx, const muon_hparams* hp, hipStream_t s, float* up
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
           if (mc)
-            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.uniform_n ? kGemmPersistent : 0), P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f,
+            MUON_TIMED(MUON_PROF_GRAM, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.persistent_n ? kGemmPersistent : 0), P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f,
                                                         first ? 1 : -1, 0.f, 0, planes, s));
           else
             MUON_TIMED(MUON_PROF_GRAM, launch_gemm_f32(P(g.prob_gram[par]), T(ts.sym), ts.n_sym, 1.f, 0.f, first ? 1 : -1, s));
@@ -215,7 +215,7 @@ int enqueue_step(muon_ctx* ctx, const muon_hparams* hp, hipStream_t s, float* up
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
           if (mc)
-            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.uniform_m ? kGemmPersistent : 0), P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, 0, planes, s));
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.persistent_m ? kGemmPersistent : 0), P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, 0, planes, s));
           else
             MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
         }
@@ -225,7 +225,7 @@ int enqueue_step(muon_ctx* ctx, const muon_hparams* hp, hipStream_t s, float* up
           const int n_app = last ? ts.n_apply_last : ts.n_apply;
           if (n_app == 0) continue;
           if (mc)
-            MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.uniform_m ? kGemmPersistent : 0), P(g.prob_apply[par * 2 + last]), T(t_app),
+            MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.persistent_m ? kGemmPersistent : 0), P(g.prob_apply[par * 2 + last]), T(t_app),
                                                               n_app, 1.f, a, first ? 0 : -1, 0.f, 1, planes, s));
           else
             MUON_TIMED(MUON_PROF_APPLY_POLY, launch_gemm_f32(P(g.prob_apply[par * 2 + last]), T(t_app), n_app, 1.f, a,

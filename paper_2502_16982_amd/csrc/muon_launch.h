@@ -24,7 +24,8 @@ hipError_t launch_norm_finalize(const MatDesc* mats, int first_mat, int n_mats, 
 // coarse: 0 = every tile of the table is 128 x 128 (two blocks per compute unit); 1 = the table mixes 256 x 256 and,
 // with kGemmStrips in `flags`, 512 x 128 tiles (one block per compute unit; the flag selects the larger LDS
 // allocation).  kGemmPersistent: one block per compute unit works through the table with stride gridDim (for launches
-// whose tiles all cost the same; with mixed K the hardware's dynamic block dispatch balances better).
+// whose tiles run K loops of nearly the same length, which the planner balances statically; with a wide spread of K
+// the hardware's dynamic block dispatch does better).
 // l_kmajor: every problem of the launch stores its L operand K-major (element (i, k) at L[k * ldl + i]).
 // planes: 1 = plain bf16; 2 or 3 = every matrix is a sum of that many bf16 planes (GemmProblem::*_plane strides).
 constexpr int kGemmStrips = 1, kGemmPersistent = 2;

@@ -31,9 +31,9 @@ struct TileSet {
   size_t sym = 0, apply = 0, apply_last = 0;
   int n_sym = 0, n_apply = 0, n_apply_last = 0;
   bool strips = false;    // the tables hold 512 x 128 tiles (the launch then needs the larger LDS allocation)
-  // every problem of the launch has the same n_pad / m_pad, i.e. every tile of the Gram product / of the other two
-  // products runs a K loop of the same length: the launch can then deal its tiles to persistent blocks statically
-  bool uniform_n = false, uniform_m = false;
+  // the K loops of the launch's tiles are of nearly the same length (Gram product: n_pad; the other two: m_pad), so
+  // the launch runs persistent blocks that take the planner's static assignment of tiles
+  bool persistent_n = false, persistent_m = false;
 };
 
 // Launch group: all matrices of one chunk.  Each product is one launch per level: the coarse launch (matrix-core
