@@ -215,9 +215,9 @@ int enqueue_step(muon_ctx* ctx, const muon_hparams* hp, hipStream_t s, float* up
           const TileSet& ts = level ? g.coarse : g.fine;
           if (ts.n_sym == 0) continue;
           if (mc)
-            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.persistent_m ? kGemmPersistent : 0), P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, a, 0, planes, s));
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_bf16(level, (ts.strips ? kGemmStrips : 0) | (ts.persistent_m ? kGemmPersistent : 0), P(g.prob_poly), T(ts.poly), ts.n_poly, c, b, -1, a, 0, planes, s));
           else
-            MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.sym), ts.n_sym, c, b, -1, s));
+            MUON_TIMED(MUON_PROF_POLY, launch_gemm_f32(P(g.prob_poly), T(ts.poly), ts.n_poly, c, b, -1, s));
         }
         for (int level = 1; level >= 0; --level) {
           const TileSet& ts = level ? g.coarse : g.fine;

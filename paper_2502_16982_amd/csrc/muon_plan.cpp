@@ -219,7 +219,7 @@ struct TableLayout {
 size_t gemm_tables_bytes_for(const MatPlan& q) {
   const int tm = q.mp / q.tile, tn = q.np / q.tile;
   const size_t sym = (size_t)tm * (tm + 1) / 2 + 1, app = (size_t)tm * tn + 1;
-  return 7 * sizeof(GemmProblem) + (sym + 2 * app) * sizeof(GemmTile);
+  return 7 * sizeof(GemmProblem) + (2 * sym + 2 * app) * sizeof(GemmTile);
 }
 
 TableLayout table_layout(const std::vector<MatPlan>& mp, size_t total_partials) {
@@ -561,16 +561,19 @@ int plan_build(Plan& plan, const muon_param* shapes, int32_t n, int32_t ns_dtype
         ts.persistent_n = steady_n;
         ts.persistent_m = steady_m;
         ts.sym = take(n_sym * sizeof(GemmTile));
+        ts.poly = take(n_sym * sizeof(GemmTile));
         ts.apply = take(n_app * sizeof(GemmTile));
         ts.apply_last = take(n_app * sizeof(GemmTile));
         // the two symmetric products share one table, dealt in the order of the Gram product (K = n)
-        // costs are evened out over a die's blocks only in tables whose launches are all persistent: where the
-        // hardware hands out the blocks the plain order measured better
+        // The two symmetric products run the same tiles but not the same K (n for the Gram product, m for the
+        // polynomial), so each gets its own table: dealt longest K first and weighted by its own K, and with the costs
+        // evened out over a die's blocks where its launch is persistent (where the hardware hands out the blocks the
+        // plain order measured better).
         const int slots = level == 1 ? plan.coarse_blocks / kXcds : 0;
-        const int sym_slots = steady_n && steady_m ? slots : 0, app_slots = steady_m ? slots : 0;
-        ts.n_sym = (int)deal_tiles(by_n, sym, sym_cuts, w_n, reinterpret_cast<GemmTile*>(img.data() + ts.sym), sym_slots);
-        ts.n_apply = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply), app_slots);
-        ts.n_apply_last = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply_last), app_slots);
+        ts.n_sym = (int)deal_tiles(by_n, sym, sym_cuts, w_n, reinterpret_cast<GemmTile*>(img.data() + ts.sym), steady_n ? slots : 0);
+        ts.n_poly = (int)deal_tiles(by_m, sym, sym_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.poly), steady_m ? slots : 0);
+        ts.n_apply = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply), steady_m ? slots : 0);
+        ts.n_apply_last = (int)deal_tiles(by_m, app, app_cuts, w_m, reinterpret_cast<GemmTile*>(img.data() + ts.apply_last), steady_m ? slots : 0);
       }
       ch.groups.push_back(g);
     }
@@ -588,8 +591,8 @@ int64_t plan_tiles(const Plan& plan, int chunk, int product, int level, int32_t*
   const bool mc = on_matrix_cores(plan.ns_dtype);
   for (const Group& g : plan.chunks[chunk].groups) {
     const TileSet& ts = level ? g.coarse : g.fine;
-    const size_t off = product <= 1 ? ts.sym : product == 2 ? ts.apply : ts.apply_last;
-    const int count = product <= 1 ? ts.n_sym : product == 2 ? ts.n_apply : ts.n_apply_last;
+    const size_t off = product == 0 ? ts.sym : product == 1 ? ts.poly : product == 2 ? ts.apply : ts.apply_last;
+    const int count = product == 0 ? ts.n_sym : product == 1 ? ts.n_poly : product == 2 ? ts.n_apply : ts.n_apply_last;
     const GemmTile* t = reinterpret_cast<const GemmTile*>(plan.image.data() + off);
     for (int i = 0; i < count; ++i, ++total) {
       if (total >= cap_records) continue;

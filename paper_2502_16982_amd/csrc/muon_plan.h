@@ -28,8 +28,8 @@ struct MatPlan {
 
 // Tile tables of one launch level (byte offsets in the table region).
 struct TileSet {
-  size_t sym = 0, apply = 0, apply_last = 0;
-  int n_sym = 0, n_apply = 0, n_apply_last = 0;
+  size_t sym = 0, poly = 0, apply = 0, apply_last = 0;     // Gram, polynomial, apply, last apply
+  int n_sym = 0, n_poly = 0, n_apply = 0, n_apply_last = 0;
   bool strips = false;    // the tables hold 512 x 128 tiles (the launch then needs the larger LDS allocation)
   // the K loops of the launch's tiles are of nearly the same length (Gram product: n_pad; the other two: m_pad), so
   // the launch runs persistent blocks that take the planner's static assignment of tiles
