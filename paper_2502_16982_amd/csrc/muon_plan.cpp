@@ -564,7 +564,6 @@ int plan_build(Plan& plan, const muon_param* shapes, int32_t n, int32_t ns_dtype
         ts.poly = take(n_sym * sizeof(GemmTile));
         ts.apply = take(n_app * sizeof(GemmTile));
         ts.apply_last = take(n_app * sizeof(GemmTile));
-        // the two symmetric products share one table, dealt in the order of the Gram product (K = n)
         // The two symmetric products run the same tiles but not the same K (n for the Gram product, m for the
         // polynomial), so each gets its own table: dealt longest K first and weighted by its own K, and with the costs
         // evened out over a die's blocks where its launch is persistent (where the hardware hands out the blocks the
